@@ -1,0 +1,185 @@
+"""TEST INFRASTRUCTURE ONLY -- the DeFT-Flatten QKV-preparation plan in plain Python.
+
+Follows Algorithm 3 (QKV Preparation of DeFT-Flatten) and Remark 3.1 of the
+paper: flatten the tree's KV depth-first, cut the flattened token sequence into
+even chunks of at most S_t tokens, group every chunk with all queries that share
+any of its tokens (KV-guided grouping), and give each node-piece inside a chunk a
+bit causal mask over that group.  Where the paper leaves the encoding open the
+following readings are used (each is also listed in the design notes):
+
+  * children are visited in ascending node id, roots in ascending node id;
+  * queries are renumbered in depth-first order (ties by caller index) so that
+    the queries whose path contains node u form one interval [q_lo[u], q_hi[u]);
+  * nodes that no query reaches, and nodes without tokens, are left out of the
+    flattened sequence;
+  * mask bit j of a segment is 1 when the j-th query of the chunk's group
+    attends to the segment (1 = valid); groups wider than 64 queries use
+    ceil(w/64) little-endian 64-bit words per segment;
+  * a query attends to its own node's tokens (paths are inclusive).
+
+Everything is integer work; the output arrays are the canonical encoding that
+the C++ planner must reproduce bit for bit.
+"""
+
+from __future__ import annotations
+
+import numpy as np
+
+
+class PlanError(ValueError):
+    pass
+
+
+def _validate(nb, nl, par, qn, ntok, chunk_size):
+    n = len(nb)
+    if n < 1 or len(nl) != n or len(par) != n:
+        raise PlanError("node table must have n_nodes >= 1 equal-length columns")
+    if chunk_size <= 0 or chunk_size % 32 != 0:
+        raise PlanError("chunk_size must be a positive multiple of 32")
+    if ntok < 0:
+        raise PlanError("ntok < 0")
+    for u in range(n):
+        if par[u] < -1 or par[u] >= n or par[u] == u:
+            raise PlanError("parent out of range")
+        if nl[u] < 0 or nb[u] < 0 or nb[u] + nl[u] > ntok:
+            raise PlanError("token range outside the cache")
+    # cycles: every node must reach a root within n steps
+    for u in range(n):
+        v, steps = u, 0
+        while v != -1:
+            v = par[v]
+            steps += 1
+            if steps > n:
+                raise PlanError("parent pointers contain a cycle")
+    # overlap of non-empty ranges
+    spans = sorted((nb[u], nb[u] + nl[u]) for u in range(n) if nl[u] > 0)
+    for a, b in zip(spans, spans[1:]):
+        if b[0] < a[1]:
+            raise PlanError("node token ranges overlap")
+    for x in qn:
+        if x < 0 or x >= n:
+            raise PlanError("query node out of range")
+
+
+def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, chunk_size=128):
+    nb = [int(x) for x in node_tok_begin]
+    nl = [int(x) for x in node_tok_len]
+    par = [int(x) for x in node_parent]
+    qn = [int(x) for x in query_node]
+    ntok = int(ntok)
+    B = int(chunk_size)
+    _validate(nb, nl, par, qn, ntok, B)
+    n, nq = len(nb), len(qn)
+
+    # 1. children lists, ascending node id
+    children = [[] for _ in range(n)]
+    roots = []
+    for u in range(n):
+        if par[u] == -1:
+            roots.append(u)
+        else:
+            children[par[u]].append(u)
+
+    # 2./3. depth-first preorder with the running query counter
+    cnt = [0] * n
+    for x in qn:
+        cnt[x] += 1
+    pre, q_lo, q_hi = [], [0] * n, [0] * n
+    ctr = 0
+    for r in roots:
+        stack = [(r, 0)]
+        q_lo[r] = ctr
+        ctr += cnt[r]
+        pre.append(r)
+        while stack:
+            u, i = stack.pop()
+            if i < len(children[u]):
+                stack.append((u, i + 1))
+                c = children[u][i]
+                q_lo[c] = ctr
+                ctr += cnt[c]
+                pre.append(c)
+                stack.append((c, 0))
+            else:
+                q_hi[u] = ctr
+    assert ctr == nq and len(pre) == n
+    rank = [0] * n
+    for i, u in enumerate(pre):
+        rank[u] = i
+    q_order = sorted(range(nq), key=lambda j: (rank[qn[j]], j))
+
+    # 4. flattened sequence: reached, non-empty nodes in preorder
+    flat_nodes = [u for u in pre if q_hi[u] > q_lo[u] and nl[u] > 0]
+    n_flat = sum(nl[u] for u in flat_nodes)
+
+    # 5./6. even chunks and the node pieces (segments) inside them
+    m = (n_flat + B - 1) // B
+    chunk_seg_ptr = [0]
+    seg_tok_begin, seg_len, seg_qlo, seg_qhi, seg_node = [], [], [], [], []
+    room = B if m > 0 else 0
+    for u in flat_nodes:
+        off = 0
+        while off < nl[u]:
+            if room == 0:
+                chunk_seg_ptr.append(len(seg_len))
+                room = B
+            take = min(room, nl[u] - off)
+            seg_tok_begin.append(nb[u] + off)
+            seg_len.append(take)
+            seg_qlo.append(q_lo[u])
+            seg_qhi.append(q_hi[u])
+            seg_node.append(u)
+            off += take
+            room -= take
+    if m > 0:
+        chunk_seg_ptr.append(len(seg_len))
+    assert len(chunk_seg_ptr) == m + 1 or (m == 0 and chunk_seg_ptr == [0])
+    nseg = len(seg_len)
+
+    # 7. KV-guided grouping: the chunk's query interval and its partial-result slots
+    chunk_qlo, chunk_qhi, chunk_slot_base = [], [], [0]
+    for c in range(m):
+        segs = range(chunk_seg_ptr[c], chunk_seg_ptr[c + 1])
+        lo = min(seg_qlo[s] for s in segs)
+        hi = max(seg_qhi[s] for s in segs)
+        chunk_qlo.append(lo)
+        chunk_qhi.append(hi)
+        chunk_slot_base.append(chunk_slot_base[-1] + (hi - lo))
+    n_slots = chunk_slot_base[-1]
+
+    # 8. bit causal masks, one run of 64-bit words per segment
+    seg_mask_ptr, seg_mask = [0], []
+    for c in range(m):
+        w = chunk_qhi[c] - chunk_qlo[c]
+        words = (w + 63) // 64
+        for s in range(chunk_seg_ptr[c], chunk_seg_ptr[c + 1]):
+            for k in range(words):
+                word = 0
+                for j in range(64):
+                    p = chunk_qlo[c] + 64 * k + j
+                    if p < chunk_qhi[c] and seg_qlo[s] <= p < seg_qhi[s]:
+                        word |= 1 << j
+                seg_mask.append(word)
+            seg_mask_ptr.append(len(seg_mask))
+
+    # 9. per query: the chunks it takes part in and where its partial results live
+    q_part_ptr, q_part_chunk, q_part_slot = [0], [], []
+    for p in range(nq):
+        for c in range(m):
+            if chunk_qlo[c] <= p < chunk_qhi[c]:
+                q_part_chunk.append(c)
+                q_part_slot.append(chunk_slot_base[c] + (p - chunk_qlo[c]))
+        q_part_ptr.append(len(q_part_chunk))
+
+    i32 = lambda a: np.asarray(a, dtype=np.int32).reshape(-1)  # noqa: E731
+    return {
+        "chunk_size": B, "n_nodes": n, "nq": nq, "n_flat": n_flat,
+        "n_chunks": m, "n_segs": nseg, "n_slots": n_slots,
+        "q_order": i32(q_order), "node_q_lo": i32(q_lo), "node_q_hi": i32(q_hi),
+        "chunk_seg_ptr": i32(chunk_seg_ptr if m > 0 else [0]),
+        "seg_tok_begin": i32(seg_tok_begin), "seg_len": i32(seg_len),
+        "seg_qlo": i32(seg_qlo), "seg_qhi": i32(seg_qhi), "seg_node": i32(seg_node),
+        "chunk_qlo": i32(chunk_qlo), "chunk_qhi": i32(chunk_qhi), "chunk_slot_base": i32(chunk_slot_base),
+        "seg_mask_ptr": i32(seg_mask_ptr), "seg_mask": np.asarray(seg_mask, dtype=np.uint64).reshape(-1),
+        "q_part_ptr": i32(q_part_ptr), "q_part_chunk": i32(q_part_chunk), "q_part_slot": i32(q_part_slot),
+    }

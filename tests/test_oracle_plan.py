@@ -1,0 +1,187 @@
+"""Pins for the oracle's DeFT-Flatten plan (CPU only).
+
+No worked numeric example of the flatten/bitmask survives in the paper's text, so the plan
+is pinned by (a) two hand-derived fixtures under tests/golden/, (b) the closed forms the paper
+gives (m = ceil(n_T/S_t), Algorithm 3; KV IO = 2 d N_tree and F_s = sum N_i / N_tree,
+Appendix A.5), (c) structural invariants (Remark 3.1: parent's queries contain the child's;
+every chunk holds S_t tokens but the last), (d) exact coverage of every (query, path-token)
+pair, counted against an independent path walk, and (e) running Algorithm 4 on the plan and
+comparing with the plain-definition oracle.
+"""
+
+import glob
+import json
+import os
+from collections import Counter
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import deft_flatten
+from oracle.plan import PlanError, flatten_plan
+from paper_2404_00242_amd import workloads as wl
+
+GOLDEN = sorted(glob.glob(os.path.join(os.path.dirname(__file__), "golden", "plan_*.json")))
+
+
+def plan_of(t, B=128):
+    return flatten_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B)
+
+
+def path_pairs(t):
+    """Multiset of (user query, physical token) pairs from walking parent pointers."""
+    c = Counter()
+    for j, u in enumerate(t.query_node):
+        u = int(u)
+        while u >= 0:
+            for r in range(int(t.node_tok_begin[u]), int(t.node_tok_begin[u] + t.node_tok_len[u])):
+                c[(j, r)] += 1
+            u = int(t.node_parent[u])
+    return c
+
+
+def plan_pairs(p, use_bits):
+    """Multiset of (user query, physical token) pairs enumerated from the plan's segments."""
+    c = Counter()
+    for ch in range(p["n_chunks"]):
+        lo = int(p["chunk_qlo"][ch])
+        for s in range(p["chunk_seg_ptr"][ch], p["chunk_seg_ptr"][ch + 1]):
+            if use_bits:
+                mp = int(p["seg_mask_ptr"][s])
+                qs = [lo + j for j in range(int(p["chunk_qhi"][ch]) - lo)
+                      if (int(p["seg_mask"][mp + j // 64]) >> (j % 64)) & 1]
+            else:
+                qs = range(int(p["seg_qlo"][s]), int(p["seg_qhi"][s]))
+            for pos in qs:
+                for r in range(int(p["seg_tok_begin"][s]), int(p["seg_tok_begin"][s] + p["seg_len"][s])):
+                    c[(int(p["q_order"][pos]), r)] += 1
+    return c
+
+
+def check_invariants(t, p, B):
+    m = p["n_chunks"]
+    assert m == -(-p["n_flat"] // B)                                  # m = ceil(n_T / S_t)
+    for ch in range(m):
+        n = int(p["seg_len"][p["chunk_seg_ptr"][ch]:p["chunk_seg_ptr"][ch + 1]].sum())
+        assert n == (B if ch < m - 1 else p["n_flat"] - B * (m - 1))  # even blocks, short tail
+        assert p["chunk_seg_ptr"][ch + 1] > p["chunk_seg_ptr"][ch]
+    # parent's query interval contains the child's
+    for u in range(t.n_nodes):
+        par = int(t.node_parent[u])
+        if par >= 0:
+            assert p["node_q_lo"][par] <= p["node_q_lo"][u] <= p["node_q_hi"][u] <= p["node_q_hi"][par]
+    assert sorted(p["q_order"].tolist()) == list(range(t.nq))
+    # every reached token in exactly one segment; the two encodings of the mask agree
+    assert plan_pairs(p, use_bits=True) == plan_pairs(p, use_bits=False) == path_pairs(t)
+    # slots: one per (chunk, query of its group), each listed once in the query's list
+    assert p["n_slots"] == int((p["chunk_qhi"] - p["chunk_qlo"]).sum()) == len(p["q_part_slot"])
+    assert sorted(p["q_part_slot"].tolist()) == list(range(p["n_slots"]))
+    for pos in range(t.nq):
+        a, b = int(p["q_part_ptr"][pos]), int(p["q_part_ptr"][pos + 1])
+        chunks = p["q_part_chunk"][a:b]
+        assert np.all(np.diff(chunks) > 0)
+        for ch, slot in zip(chunks, p["q_part_slot"][a:b]):
+            assert slot == p["chunk_slot_base"][ch] + pos - p["chunk_qlo"][ch]
+
+
+@pytest.mark.parametrize("path", GOLDEN, ids=[os.path.basename(g) for g in GOLDEN])
+def test_hand_derived_fixtures(path):
+    g = json.load(open(path))
+    p = flatten_plan(**g["input"])
+    for key, want in g["expect"].items():
+        got = p[key]
+        if isinstance(want, list):
+            assert np.asarray(got).tolist() == want, key
+        else:
+            assert int(got) == want, key
+
+
+def test_fixture_files_exist():
+    assert len(GOLDEN) >= 2
+
+
+@pytest.mark.parametrize("cfg,B", [(1, 128), (1, 32), (2, 128), (3, 128), (3, 64), (4, 128), (5, 128), (5, 512)])
+def test_benchmark_configs_closed_forms(cfg, B):
+    t = wl.make_config(cfg)
+    p = plan_of(t, B)
+    if cfg in (1, 2, 3):
+        check_invariants(t, p, B)
+    # every node of these trees is reached, so the flattened length is the whole tree: KV IO = 2 d N_tree
+    assert p["n_flat"] == int(t.node_tok_len.sum()) == t.ntok
+    assert p["n_chunks"] == -(-t.ntok // B)
+    # share factor F_s = sum_i N_i / N_tree from the plan's segments equals the one from path walking
+    seg_pairs = int((p["seg_len"].astype(np.int64) * (p["seg_qhi"] - p["seg_qlo"])).sum())
+    assert seg_pairs == wl.path_token_count(t)
+    if cfg == 2:
+        assert abs(seg_pairs / p["n_flat"] - 9.333) < 1e-3          # (20*4256)/9120
+        assert p["n_slots"] == 699 and p["n_segs"] == 92
+    if cfg == 3:
+        assert t.ntok == 4064 and p["n_slots"] == 2048 if B == 128 else True
+    if cfg == 1 and B == 128:
+        assert (p["n_chunks"], p["n_segs"], p["n_slots"]) == (3, 6, 12)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_forests_invariants_and_coverage(seed):
+    t = wl.random_tree(seed, n_nodes=2 + seed % 17, max_len=90, nq=1 + (seed * 7) % 23, n_roots=1 + seed % 3)
+    for B in (32, 64):
+        check_invariants(t, plan_of(t, B), B)
+
+
+def test_wide_groups_use_several_mask_words():
+    # 150 queries on the leaves of a star: the root's chunks carry ceil(150/64) = 3 words per segment
+    n = 151
+    t = wl._finish("star", [100] + [3] * 150, [-1] + [0] * 150, list(range(1, n)), 2, 1, 8, 1)
+    p = plan_of(t, 32)
+    check_invariants(t, p, 32)
+    assert p["seg_mask_ptr"][1] - p["seg_mask_ptr"][0] == 3
+    assert int(p["seg_mask"][0]) == 2**64 - 1 and int(p["seg_mask"][2]) == 2**(150 - 128) - 1
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_algorithm4_on_the_plan_reproduces_the_definition(seed):
+    t = wl.random_tree(200 + seed, n_nodes=4 + 2 * seed, max_len=40, nq=6, Hq=4, Hkv=2, d=8, n_roots=1 + seed % 2)
+    Q, K, V = (x.float().numpy() for x in wl.make_qkv(t))
+    ref = oracle.tree_attention(Q, K, V, t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node)
+    got = deft_flatten.attention_by_plan(plan_of(t, 32), Q, K, V)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+
+
+def test_sibling_order_changes_the_plan_but_not_the_coverage():
+    t = wl.config1_tiny()
+    p1 = plan_of(t, 32)
+    # swap the ids of leaves 1 and 4 (and their cache ranges stay with the node)
+    nb = t.node_tok_begin.copy(); nb[[1, 4]] = nb[[4, 1]]
+    t2 = wl._finish("swapped", t.node_tok_len, t.node_parent, t.query_node, 4, 4, 64, 1, begins=nb, ntok=t.ntok)
+    p2 = plan_of(t2, 32)
+    check_invariants(t2, p2, 32)
+    assert p1["seg_tok_begin"].tolist() != p2["seg_tok_begin"].tolist()
+
+
+@pytest.mark.parametrize("bad", [
+    dict(node_parent=[0, 0]),                       # self parent
+    dict(node_parent=[1, 0]),                       # cycle
+    dict(node_parent=[-1, 5]),                      # parent out of range
+    dict(node_tok_begin=[0, 2]),                    # overlap
+    dict(node_tok_len=[4, 9]),                      # range beyond ntok
+    dict(node_tok_len=[4, -1]),                     # negative length
+    dict(query_node=[2]),                           # query node out of range
+    dict(query_node=[-1]),
+    dict(chunk_size=0), dict(chunk_size=48), dict(chunk_size=-32),
+])
+def test_invalid_inputs_are_rejected(bad):
+    args = dict(node_tok_begin=[0, 4], node_tok_len=[4, 4], node_parent=[-1, 0], query_node=[1], ntok=8, chunk_size=32)
+    args.update(bad)
+    with pytest.raises(PlanError):
+        flatten_plan(**args)
+
+
+def test_degenerate_plans():
+    # no queries: nothing is reached, nothing is planned
+    p = flatten_plan([0], [10], [-1], [], 10, 32)
+    assert (p["n_chunks"], p["n_segs"], p["n_slots"], p["n_flat"]) == (0, 0, 0, 0)
+    assert p["chunk_seg_ptr"].tolist() == [0] and p["q_part_ptr"].tolist() == [0]
+    # a query whose path has no tokens
+    p = flatten_plan([0, 0], [0, 0], [-1, 0], [1], 0, 32)
+    assert p["n_chunks"] == 0 and p["q_part_ptr"].tolist() == [0, 0]
