@@ -1,0 +1,175 @@
+/*
+ * libdeft -- tree-attention decode (DeFT-Flatten) for AMD MI355X (gfx950), C ABI.
+ *
+ * Every query token of a decoding tree attends over the KV cache along its own
+ * root-to-node path.  The work is split as in the paper: a host-side QKV
+ * preparation phase (deft_plan) that groups each piece of KV with all queries
+ * sharing it (KV-guided grouping) after flattening the tree depth-first and
+ * cutting it into even chunks tagged with bit causal masks (Flattened Tree KV
+ * Splitting), and a device-side attention phase (deft_tree_attn_decode) of
+ * per-chunk partial attention followed by a log-sum-exp global reduction.
+ *
+ * Conventions
+ *   - All functions return 0 (DEFT_OK) or a negative deft_status; nothing throws.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *     memory on the current device.  The library allocates no device memory:
+ *     Q/K/V/O, the plan's device image and the workspace all belong to the caller.
+ *   - deft_tree_attn_decode only enqueues kernels on the given stream; it does not
+ *     synchronise.  Calls that share a workspace must be ordered by the caller.
+ */
+#ifndef DEFT_H_
+#define DEFT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum deft_status {
+    DEFT_OK = 0,
+    DEFT_EINVAL = -1,      /* null pointer, bad size, malformed tree, unsupported head shape */
+    DEFT_ENOMEM = -2,      /* host allocation failed */
+    DEFT_EWORKSPACE = -3,  /* workspace or plan image buffer too small */
+    DEFT_EHIP = -4,        /* a HIP runtime call or kernel launch failed */
+    DEFT_ENOTREADY = -5    /* no device image was built for this Hq/Hkv ratio (call deft_plan_upload) */
+} deft_status;
+
+/* Output element type of deft_tree_attn_decode (flags argument). */
+#define DEFT_OUT_BF16 0u
+#define DEFT_OUT_F32 1u
+
+#define DEFT_DEFAULT_CHUNK 128 /* the paper's default KV block size (chunk-size ablation, Fig. 11) */
+#define DEFT_MAX_CHUNK 4096
+
+typedef struct deft_plan_s deft_plan_t;
+
+/*
+ * Host view of the canonical plan (borrowed pointers, valid until deft_plan_destroy).
+ * The arrays are the outputs of the QKV Preparation Phase of DeFT-Flatten
+ * (Algorithm 3; Remark 3.1), encoded as follows.
+ *
+ *   Depth-first flatten: children in ascending node id, roots ascending.  Queries are
+ *   renumbered in that order ("plan positions", ties by caller index) so that the queries
+ *   whose path contains node u are exactly positions [node_q_lo[u], node_q_hi[u]);
+ *   q_order[p] is the caller's index of plan position p.  Nodes no query reaches and nodes
+ *   without tokens are left out; n_flat is the flattened token count.
+ *
+ *   Even block-wise split: chunk c covers flattened positions [c*S, min((c+1)*S, n_flat)),
+ *   n_chunks = ceil(n_flat / S).  The node pieces inside it are segments
+ *   chunk_seg_ptr[c] .. chunk_seg_ptr[c+1]-1 (SubInfo): physical rows
+ *   [seg_tok_begin, seg_tok_begin + seg_len) of node seg_node, shared by plan positions
+ *   [seg_qlo, seg_qhi).
+ *
+ *   KV-guided grouping: chunk c is grouped with plan positions [chunk_qlo[c], chunk_qhi[c])
+ *   (KVMapQ); its partial results occupy slots chunk_slot_base[c] + (p - chunk_qlo[c]).
+ *   For plan position p, q_part_chunk / q_part_slot [q_part_ptr[p] .. q_part_ptr[p+1]) list
+ *   the chunks it takes part in (QMapKV) and the slots to reduce.
+ *
+ *   Bit causal mask: segment s owns words seg_mask[seg_mask_ptr[s] .. seg_mask_ptr[s+1]),
+ *   ceil(w/64) little-endian 64-bit words for a group of w queries; bit j = 1 means the
+ *   j-th query of the chunk's group attends to the segment.
+ */
+typedef struct deft_plan_view {
+    int32_t chunk_size, n_nodes, nq, n_flat, n_chunks, n_segs, n_slots, n_mask_words;
+    const int32_t *q_order;         /* [nq] */
+    const int32_t *node_q_lo;       /* [n_nodes] */
+    const int32_t *node_q_hi;       /* [n_nodes] */
+    const int32_t *chunk_seg_ptr;   /* [n_chunks+1] ([1] = {0} when n_chunks == 0) */
+    const int32_t *seg_tok_begin;   /* [n_segs] */
+    const int32_t *seg_len;         /* [n_segs] */
+    const int32_t *seg_qlo;         /* [n_segs] */
+    const int32_t *seg_qhi;         /* [n_segs] */
+    const int32_t *seg_node;        /* [n_segs] */
+    const int32_t *chunk_qlo;       /* [n_chunks] */
+    const int32_t *chunk_qhi;       /* [n_chunks] */
+    const int32_t *chunk_slot_base; /* [n_chunks+1] */
+    const int32_t *seg_mask_ptr;    /* [n_segs+1] */
+    const uint64_t *seg_mask;       /* [n_mask_words] */
+    const int32_t *q_part_ptr;      /* [nq+1] */
+    const int32_t *q_part_chunk;    /* [n_slots] */
+    const int32_t *q_part_slot;     /* [n_slots] */
+} deft_plan_view_t;
+
+/*
+ * QKV Preparation Phase of DeFT-Flatten (Algorithm 3; Section 3.3, Remark 3.1).
+ *
+ * node_tok_begin/len/parent : host int32[n_nodes].  Node u owns physical cache rows
+ *     [begin, begin+len) of K and V; parent is a node id or -1 for a root (forests allowed).
+ *     Ranges of non-empty nodes must lie in [0, ntok) and must not overlap; ids need not be
+ *     in topological order.
+ * query_node : host int32[nq] (may be NULL when nq == 0).  Query j attends over all tokens
+ *     of all nodes on the path root -> query_node[j], that node included.  Several queries
+ *     may share a node and may sit on inner nodes.
+ * chunk_size : S_t, tokens per chunk; 0 selects DEFT_DEFAULT_CHUNK; otherwise a positive
+ *     multiple of 32, at most DEFT_MAX_CHUNK.
+ * flags      : reserved, must be 0.
+ * out_plan   : receives a host object owned by the library; release with deft_plan_destroy.
+ *     The plan is immutable, depends on the tree only, and can be reused for every layer
+ *     and every call that sees the same tree.
+ * Errors: DEFT_EINVAL for any malformed input (null pointer, n_nodes < 1, nq < 0, parent out
+ *     of range or cyclic, range outside the cache or overlapping, query node out of range,
+ *     bad chunk_size); DEFT_ENOMEM.  *out_plan is NULL on error.
+ */
+int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_len, const int32_t *node_parent,
+              int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size,
+              uint32_t flags, deft_plan_t **out_plan);
+
+/* Fills *out with borrowed host pointers to the canonical arrays described above. */
+int deft_plan_view(const deft_plan_t *plan, deft_plan_view_t *out);
+
+/*
+ * The device image of a plan: the arrays the kernels read (segment table, chunk groups,
+ * slot lists, query order) plus the launch schedule for a given ratio Hq/Hkv (how the
+ * rows "query x query-head of one KV head" of each chunk's group are tiled over waves).
+ * deft_plan_device_bytes returns the size the caller must provide (0 on bad arguments);
+ * deft_plan_upload packs the image on the host and copies it into dev_image (device
+ * memory, 16-byte aligned) on `stream` (a hipStream_t, NULL = default stream), waiting
+ * for the copy to finish before returning.  One image serves one Hq/Hkv ratio; a plan
+ * may be uploaded for several.
+ * Errors: DEFT_EINVAL (null, Hq <= 0, Hkv <= 0, Hq % Hkv != 0), DEFT_EWORKSPACE (bytes
+ * too small), DEFT_EHIP.
+ */
+size_t deft_plan_device_bytes(const deft_plan_t *plan, int32_t Hq, int32_t Hkv);
+int deft_plan_upload(deft_plan_t *plan, int32_t Hq, int32_t Hkv, void *dev_image, size_t bytes, void *stream);
+
+/* Bytes of device workspace deft_tree_attn_decode needs (fp32 partial attention, running
+ * maxima and sums per (slot, query head)); 0 on bad arguments. */
+size_t deft_workspace_bytes(const deft_plan_t *plan, int32_t Hq, int32_t Hkv, int32_t d);
+
+/*
+ * Attention Calculation Phase of DeFT-Flatten (Algorithm 4): stage 1 computes, for every
+ * QKV group, the masked partial attention of the group's queries over the chunk with an
+ * online softmax (bf16 inputs, fp32 accumulation); stage 2 is the tree-topology-aware
+ * global reduction of eq. 1 over each query's partial results.  The result equals
+ * softmax(scale * q K^T) V over exactly the tokens on each query's path (Section 3.1).
+ *
+ * dev_image : device image written by deft_plan_upload for the same Hq/Hkv ratio.
+ * q         : device bf16 [nq, Hq, d], caller's query order.
+ * k, v      : device bf16 [ntok, Hkv, d], row-major, head dimension contiguous; node u's
+ *             tokens are rows [node_tok_begin[u], +node_tok_len[u]).
+ * o         : device [nq, Hq, d], bf16 (DEFT_OUT_BF16) or float (DEFT_OUT_F32), caller's
+ *             query order.  A query whose path holds no token gets zeros.
+ * d         : 64 or 128.  Hq % Hkv == 0.
+ * scale     : softmax scale; <= 0 selects 1/sqrt(d).
+ * workspace : device memory of at least deft_workspace_bytes(plan, Hq, Hkv, d), 16-byte
+ *             aligned; contents are scratch.
+ * stream    : hipStream_t (NULL = default stream).  Kernels are enqueued, not awaited.
+ * Errors: DEFT_EINVAL, DEFT_ENOTREADY, DEFT_EWORKSPACE, DEFT_EHIP (deft_last_hip_error
+ * gives the runtime's text).  Nothing is launched when an error is returned, except that a
+ * launch failure may leave earlier kernels of the same call enqueued.
+ */
+int deft_tree_attn_decode(const deft_plan_t *plan, const void *dev_image, const void *q, const void *k,
+                          const void *v, void *o, int32_t Hq, int32_t Hkv, int32_t d, float scale,
+                          uint32_t flags, void *workspace, size_t workspace_bytes, void *stream);
+
+void deft_plan_destroy(deft_plan_t *plan);
+
+const char *deft_strerror(int status);
+const char *deft_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEFT_H_ */

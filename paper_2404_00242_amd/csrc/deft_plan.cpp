@@ -1,0 +1,368 @@
+// Host side of libdeft: the QKV Preparation Phase of DeFT-Flatten (Algorithm 3, Remark 3.1)
+// and the launch schedule derived from it.  Pure integer work, no device calls.
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <numeric>
+
+#include "deft_internal.h"
+
+namespace {
+
+struct Range {
+    int64_t begin, end;
+};
+
+// Depth-first preorder over a forest given as parent pointers.  Children are visited in
+// ascending id, roots in ascending id.  Returns false when some node is not reachable from a
+// root, i.e. the parent pointers contain a cycle.
+bool preorder(const int32_t *parent, int32_t n, std::vector<int32_t> &order, std::vector<int32_t> &first_child,
+              std::vector<int32_t> &next_sibling) {
+    // sibling lists in ascending id: walk ids downwards and push to the front
+    first_child.assign(n, -1);
+    next_sibling.assign(n, -1);
+    int32_t first_root = -1;
+    for (int32_t u = n - 1; u >= 0; --u) {
+        int32_t p = parent[u];
+        if (p < 0) {
+            next_sibling[u] = first_root;
+            first_root = u;
+        } else {
+            next_sibling[u] = first_child[p];
+            first_child[p] = u;
+        }
+    }
+    order.clear();
+    order.reserve(n);
+    std::vector<int32_t> stack;
+    for (int32_t r = first_root; r >= 0; r = next_sibling[r]) {
+        stack.push_back(r);
+        while (!stack.empty()) {
+            int32_t u = stack.back();
+            stack.pop_back();
+            order.push_back(u);
+            // push children so that the smallest id is popped first
+            size_t mark = stack.size();
+            for (int32_t c = first_child[u]; c >= 0; c = next_sibling[c]) stack.push_back(c);
+            std::reverse(stack.begin() + (ptrdiff_t)mark, stack.end());
+        }
+    }
+    return (int32_t)order.size() == n;
+}
+
+}  // namespace
+
+extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_len, const int32_t *node_parent,
+                         int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size,
+                         uint32_t flags, deft_plan_t **out_plan) {
+    if (out_plan) *out_plan = nullptr;
+    if (!out_plan || !node_tok_begin || !node_tok_len || !node_parent) return DEFT_EINVAL;
+    if (n_nodes < 1 || nq < 0 || ntok < 0 || flags != 0) return DEFT_EINVAL;
+    if (nq > 0 && !query_node) return DEFT_EINVAL;
+    if (chunk_size == 0) chunk_size = DEFT_DEFAULT_CHUNK;
+    if (chunk_size < 0 || chunk_size % 32 != 0 || chunk_size > DEFT_MAX_CHUNK) return DEFT_EINVAL;
+
+    try {
+        const int32_t n = n_nodes;
+        // ---- validation -------------------------------------------------------------------
+        std::vector<Range> spans;
+        for (int32_t u = 0; u < n; ++u) {
+            int32_t p = node_parent[u];
+            if (p < -1 || p >= n || p == u) return DEFT_EINVAL;
+            int64_t b = node_tok_begin[u], len = node_tok_len[u];
+            if (b < 0 || len < 0 || b + len > (int64_t)ntok) return DEFT_EINVAL;
+            if (len > 0) spans.push_back({b, b + len});
+        }
+        std::sort(spans.begin(), spans.end(), [](const Range &a, const Range &b) { return a.begin < b.begin; });
+        for (size_t i = 1; i < spans.size(); ++i)
+            if (spans[i].begin < spans[i - 1].end) return DEFT_EINVAL;
+        for (int32_t j = 0; j < nq; ++j)
+            if (query_node[j] < 0 || query_node[j] >= n) return DEFT_EINVAL;
+
+        std::vector<int32_t> pre, first_child, next_sibling;
+        if (!preorder(node_parent, n, pre, first_child, next_sibling)) return DEFT_EINVAL;  // cycle
+
+        deft_plan_t *P = new deft_plan_s();
+        std::unique_ptr<deft_plan_t> guard(P);
+        P->chunk_size = chunk_size;
+        P->n_nodes = n;
+        P->nq = nq;
+        P->ntok = ntok;
+
+        // ---- depth-first renumbering of the queries ------------------------------------------
+        // A node's own queries come first, then its subtrees, so the queries whose path contains u
+        // are one interval.  q_hi[u] = q_lo[u] + (number of queries in u's subtree).
+        std::vector<int32_t> own(n, 0), sub(n, 0);
+        for (int32_t j = 0; j < nq; ++j) ++own[query_node[j]];
+        sub = own;
+        for (int32_t i = n - 1; i >= 0; --i) {  // reverse preorder: children before parents
+            int32_t u = pre[i], p = node_parent[u];
+            if (p >= 0) sub[p] += sub[u];
+        }
+        P->node_q_lo.assign(n, 0);
+        P->node_q_hi.assign(n, 0);
+        std::vector<int32_t> own_begin(n, 0);
+        {
+            // In preorder a node's interval starts where the previous node's own queries end or,
+            // when leaving subtrees, where those subtrees end: a running counter does both.
+            int32_t ctr = 0;
+            for (int32_t i = 0; i < n; ++i) {
+                int32_t u = pre[i];
+                P->node_q_lo[u] = ctr;
+                P->node_q_hi[u] = ctr + sub[u];
+                own_begin[u] = ctr;
+                ctr += own[u];
+            }
+        }
+        P->q_order.assign(nq, 0);
+        {
+            std::vector<int32_t> cursor = own_begin;  // next free plan position among u's own queries
+            for (int32_t j = 0; j < nq; ++j) P->q_order[cursor[query_node[j]]++] = j;
+        }
+
+        // ---- flatten + even block-wise split -------------------------------------------------
+        const int32_t S = chunk_size;
+        int64_t flat = 0;
+        int32_t room = 0;  // tokens still free in the open chunk
+        for (int32_t i = 0; i < n; ++i) {
+            int32_t u = pre[i];
+            if (P->node_q_hi[u] == P->node_q_lo[u] || node_tok_len[u] == 0) continue;
+            int32_t done = 0, len = node_tok_len[u];
+            while (done < len) {
+                if (room == 0) {
+                    P->chunk_seg_ptr.push_back(P->n_segs());
+                    room = S;
+                }
+                int32_t take = std::min(room, len - done);
+                P->seg_tok_begin.push_back(node_tok_begin[u] + done);
+                P->seg_len.push_back(take);
+                P->seg_qlo.push_back(P->node_q_lo[u]);
+                P->seg_qhi.push_back(P->node_q_hi[u]);
+                P->seg_node.push_back(u);
+                done += take;
+                room -= take;
+            }
+            flat += len;
+        }
+        if (flat > INT32_MAX) return DEFT_EINVAL;
+        P->n_flat = (int32_t)flat;
+        P->chunk_seg_ptr.push_back(P->n_segs());  // closes the last chunk; {0} when there is none
+        const int32_t m = (int32_t)P->chunk_seg_ptr.size() - 1;
+
+        // ---- KV-guided grouping: the queries of each chunk, and the slots of their partials ----
+        P->chunk_qlo.resize(m);
+        P->chunk_qhi.resize(m);
+        P->chunk_slot_base.assign(m + 1, 0);
+        int64_t slots = 0;
+        for (int32_t c = 0; c < m; ++c) {
+            int32_t lo = INT32_MAX, hi = INT32_MIN;
+            for (int32_t s = P->chunk_seg_ptr[c]; s < P->chunk_seg_ptr[c + 1]; ++s) {
+                lo = std::min(lo, P->seg_qlo[s]);
+                hi = std::max(hi, P->seg_qhi[s]);
+            }
+            P->chunk_qlo[c] = lo;
+            P->chunk_qhi[c] = hi;
+            slots += hi - lo;
+            if (slots > INT32_MAX) return DEFT_EINVAL;
+            P->chunk_slot_base[c + 1] = (int32_t)slots;
+        }
+
+        // ---- bit causal masks --------------------------------------------------------------------
+        P->seg_mask_ptr.assign(1, 0);
+        for (int32_t c = 0; c < m; ++c) {
+            const int32_t lo = P->chunk_qlo[c], w = P->chunk_qhi[c] - lo;
+            const int32_t words = (w + 63) / 64;
+            for (int32_t s = P->chunk_seg_ptr[c]; s < P->chunk_seg_ptr[c + 1]; ++s) {
+                const int32_t a = P->seg_qlo[s] - lo, b = P->seg_qhi[s] - lo;  // bits [a, b) are set
+                for (int32_t k = 0; k < words; ++k) {
+                    int32_t x = std::max(a, 64 * k) - 64 * k, y = std::min(b, 64 * (k + 1)) - 64 * k;
+                    uint64_t word = 0;
+                    if (y > x) word = (y - x == 64 ? ~0ull : ((1ull << (y - x)) - 1)) << x;
+                    P->seg_mask.push_back(word);
+                }
+                if (P->seg_mask.size() > (size_t)INT32_MAX) return DEFT_EINVAL;
+                P->seg_mask_ptr.push_back((int32_t)P->seg_mask.size());
+            }
+        }
+
+        // ---- per query: chunks it takes part in (ascending) and the slots to reduce -------------
+        P->q_part_ptr.assign(nq + 1, 0);
+        for (int32_t c = 0; c < m; ++c)
+            for (int32_t p = P->chunk_qlo[c]; p < P->chunk_qhi[c]; ++p) ++P->q_part_ptr[p + 1];
+        for (int32_t p = 0; p < nq; ++p) P->q_part_ptr[p + 1] += P->q_part_ptr[p];
+        P->q_part_chunk.assign((size_t)slots, 0);
+        P->q_part_slot.assign((size_t)slots, 0);
+        {
+            std::vector<int32_t> cursor(P->q_part_ptr.begin(), P->q_part_ptr.end() - 1);
+            for (int32_t c = 0; c < m; ++c)
+                for (int32_t p = P->chunk_qlo[c]; p < P->chunk_qhi[c]; ++p) {
+                    int32_t at = cursor[p]++;
+                    P->q_part_chunk[at] = c;
+                    P->q_part_slot[at] = P->chunk_slot_base[c] + (p - P->chunk_qlo[c]);
+                }
+        }
+
+        *out_plan = guard.release();
+        return DEFT_OK;
+    } catch (const std::bad_alloc &) {
+        return DEFT_ENOMEM;
+    } catch (...) {
+        return DEFT_EINVAL;
+    }
+}
+
+extern "C" int deft_plan_view(const deft_plan_t *P, deft_plan_view_t *out) {
+    if (!P || !out) return DEFT_EINVAL;
+    out->chunk_size = P->chunk_size;
+    out->n_nodes = P->n_nodes;
+    out->nq = P->nq;
+    out->n_flat = P->n_flat;
+    out->n_chunks = P->n_chunks();
+    out->n_segs = P->n_segs();
+    out->n_slots = P->n_slots();
+    out->n_mask_words = (int32_t)P->seg_mask.size();
+    out->q_order = P->q_order.data();
+    out->node_q_lo = P->node_q_lo.data();
+    out->node_q_hi = P->node_q_hi.data();
+    out->chunk_seg_ptr = P->chunk_seg_ptr.data();
+    out->seg_tok_begin = P->seg_tok_begin.data();
+    out->seg_len = P->seg_len.data();
+    out->seg_qlo = P->seg_qlo.data();
+    out->seg_qhi = P->seg_qhi.data();
+    out->seg_node = P->seg_node.data();
+    out->chunk_qlo = P->chunk_qlo.data();
+    out->chunk_qhi = P->chunk_qhi.data();
+    out->chunk_slot_base = P->chunk_slot_base.data();
+    out->seg_mask_ptr = P->seg_mask_ptr.data();
+    out->seg_mask = P->seg_mask.data();
+    out->q_part_ptr = P->q_part_ptr.data();
+    out->q_part_chunk = P->q_part_chunk.data();
+    out->q_part_slot = P->q_part_slot.data();
+    return DEFT_OK;
+}
+
+extern "C" void deft_plan_destroy(deft_plan_t *plan) { delete plan; }
+
+extern "C" const char *deft_strerror(int status) {
+    switch (status) {
+        case DEFT_OK: return "ok";
+        case DEFT_EINVAL: return "invalid argument";
+        case DEFT_ENOMEM: return "out of host memory";
+        case DEFT_EWORKSPACE: return "workspace or plan image buffer too small";
+        case DEFT_EHIP: return "HIP runtime error";
+        case DEFT_ENOTREADY: return "no plan image was built for this Hq/Hkv ratio";
+        default: return "unknown status";
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Launch schedule.  The rows of a chunk's group, seen from one KV head, are (query of the group) x
+// (the G query heads that read this KV head): R = w * G rows, tiled 16 at a time (the N dimension
+// of the 16x16x32 MFMA).  A wave carries up to NT row tiles through the whole chunk, so narrow
+// groups run with few registers per wave and wide groups are cut into several waves that re-read
+// the chunk from L2.  The kernel numbers its workgroups item * Hkv + kv_head, so the items that
+// re-read one chunk for one head sit Hkv workgroups apart; with Hkv a multiple of 8 and workgroups
+// dealt round-robin to the 8 XCDs they meet in the same L2.
+// ------------------------------------------------------------------------------------------------
+namespace deft {
+
+static size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
+    S.group = G;
+    const int32_t m = P->n_chunks();
+    static const int kClasses[3] = {1, 2, 4};
+    std::vector<std::vector<int32_t>> items(3);
+    for (int32_t c = 0; c < m; ++c) {
+        const int64_t rows = (int64_t)(P->chunk_qhi[c] - P->chunk_qlo[c]) * G;
+        const int32_t tiles = (int32_t)((rows + 15) / 16);
+        if (tiles <= 0) continue;
+        int cls = tiles == 1 ? 0 : (tiles == 2 ? 1 : 2);
+        const int nt = kClasses[cls];
+        for (int32_t t0 = 0; t0 < tiles; t0 += nt) {
+            int32_t cnt = std::min(nt, tiles - t0);
+            items[cls].push_back(c);
+            items[cls].push_back(t0 | (cnt << 24));
+        }
+    }
+
+    size_t off = 0;
+    auto place = [&](size_t count) {
+        size_t at = off;
+        off = align16(off + count * sizeof(int32_t));
+        return at;
+    };
+    const int32_t nseg = P->n_segs(), nq = P->nq, slots = P->n_slots();
+    S.off_chunk_seg_ptr = place(m + 1);
+    S.off_seg_tok_begin = place(nseg);
+    S.off_seg_len = place(nseg);
+    S.off_seg_qlo = place(nseg);
+    S.off_seg_qhi = place(nseg);
+    S.off_chunk_qlo = place(m);
+    S.off_chunk_qhi = place(m);
+    S.off_chunk_slot_base = place(m + 1);
+    S.off_q_order = place(nq);
+    S.off_q_part_ptr = place(nq + 1);
+    S.off_q_part_slot = place(slots);
+    S.lists.clear();
+    for (int k = 0; k < 3; ++k) {
+        ItemList L;
+        L.nt = kClasses[k];
+        L.n_items = (int32_t)(items[k].size() / 2);
+        L.offset = place(items[k].size());
+        S.lists.push_back(L);
+    }
+    S.bytes = std::max<size_t>(off, 16);
+    S.host_image.assign(S.bytes, 0);
+    auto put = [&](size_t at, const std::vector<int32_t> &v) {
+        if (!v.empty()) std::memcpy(S.host_image.data() + at, v.data(), v.size() * sizeof(int32_t));
+    };
+    put(S.off_chunk_seg_ptr, P->chunk_seg_ptr);
+    put(S.off_seg_tok_begin, P->seg_tok_begin);
+    put(S.off_seg_len, P->seg_len);
+    put(S.off_seg_qlo, P->seg_qlo);
+    put(S.off_seg_qhi, P->seg_qhi);
+    put(S.off_chunk_qlo, P->chunk_qlo);
+    put(S.off_chunk_qhi, P->chunk_qhi);
+    put(S.off_chunk_slot_base, P->chunk_slot_base);
+    put(S.off_q_order, P->q_order);
+    put(S.off_q_part_ptr, P->q_part_ptr);
+    put(S.off_q_part_slot, P->q_part_slot);
+    for (int k = 0; k < 3; ++k) put(S.lists[k].offset, items[k]);
+}
+
+const Schedule *get_schedule(const deft_plan_t *plan, int32_t group) {
+    std::lock_guard<std::mutex> lock(plan->mu);
+    auto it = plan->schedules.find(group);
+    if (it == plan->schedules.end()) {
+        Schedule S;
+        build_schedule(plan, group, S);
+        it = plan->schedules.emplace(group, std::move(S)).first;
+    }
+    return &it->second;
+}
+
+const Schedule *find_schedule(const deft_plan_t *plan, int32_t group) {
+    std::lock_guard<std::mutex> lock(plan->mu);
+    auto it = plan->schedules.find(group);
+    return it == plan->schedules.end() ? nullptr : &it->second;
+}
+
+}  // namespace deft
+
+extern "C" size_t deft_plan_device_bytes(const deft_plan_t *plan, int32_t Hq, int32_t Hkv) {
+    if (!plan || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return 0;
+    try {
+        return deft::get_schedule(plan, Hq / Hkv)->bytes;
+    } catch (...) {
+        return 0;
+    }
+}
+
+extern "C" size_t deft_workspace_bytes(const deft_plan_t *plan, int32_t Hq, int32_t Hkv, int32_t d) {
+    if (!plan || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || (d != 64 && d != 128)) return 0;
+    const size_t rows = (size_t)plan->n_slots() * (size_t)Hq;
+    // acc [slots, Hq, d] + m [slots, Hq] + l [slots, Hq], fp32; never zero so callers can allocate it
+    return std::max<size_t>(16, (rows * (size_t)d + 2 * rows) * sizeof(float) + 32);
+}

@@ -1,0 +1,177 @@
+"""HIP path (through the C ABI) against the fp64 oracle, element by element.  Needs an MI355X.
+
+Tolerance (bf16 inputs, fp32 accumulation, bf16 probabilities in the P.V product):
+  * the five benchmark configurations: max |err| <= 2e-3 over all elements AND, per (query, head)
+    row, ||err||_2 / ||ref||_2 <= 1e-2;
+  * arbitrary small trees, whose short paths give outputs of magnitude O(1) where one bf16 ulp
+    already exceeds 2e-3: element-wise |err| <= 2e-3 + 1e-2 |ref| and the same row-relative bound.
+"""
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle.plan import flatten_plan
+from paper_2404_00242_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ABS_TOL, REL_TOL = 2e-3, 1e-2
+
+
+def run_gpu(t, Q, K, V, chunk_size=0, out_dtype=torch.bfloat16, scale=0.0):
+    dev = torch.device("cuda:0")
+    plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, chunk_size)
+    q, k, v = Q.to(dev), K.to(dev), V.to(dev)
+    o = binding.deft_tree_attn_decode(plan, q, k, v, out_dtype=out_dtype, scale=scale)
+    torch.cuda.synchronize()
+    return o.float().cpu().numpy().astype(np.float64), plan
+
+
+def reference(t, Q, K, V, scale=None):
+    return oracle.tree_attention(Q, K, V, t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, scale=scale)
+
+
+def errors(got, ref):
+    err = np.abs(got - ref)
+    num = np.sqrt(((got - ref) ** 2).sum(-1))
+    den = np.sqrt((ref ** 2).sum(-1))
+    rel = np.where(den > 0, num / np.maximum(den, 1e-300), np.where(num > 0, np.inf, 0.0))
+    return err, rel
+
+
+def check(got, ref, strict):
+    assert np.isfinite(got).all()
+    err, rel = errors(got, ref)
+    print(f"    max|err|={err.max():.3e} max row-rel={rel.max():.3e} max|ref|={np.abs(ref).max():.3f}", flush=True)
+    if strict:
+        assert err.max() <= ABS_TOL
+    else:
+        assert (err <= ABS_TOL + REL_TOL * np.abs(ref)).all()
+    assert rel.max() <= REL_TOL
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_benchmark_configs_match_oracle(cfg):
+    t = wl.make_config(cfg)
+    print(f"\n  config {cfg}: {t.name} ntok={t.ntok} nq={t.nq} Hq={t.Hq} Hkv={t.Hkv} d={t.d}", flush=True)
+    Q, K, V = wl.make_qkv(t)
+    got, plan = run_gpu(t, Q, K, V)
+    ref = reference(t, Q, K, V)
+    check(got, ref, strict=True)
+    # the plan the kernels ran on is the oracle's plan, bit for bit
+    want = flatten_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, 128)
+    view = plan.view()
+    for key in ("seg_tok_begin", "seg_len", "seg_qlo", "seg_qhi", "chunk_qlo", "chunk_qhi", "seg_mask",
+                "q_part_slot", "q_order"):
+        assert np.array_equal(view[key], want[key]), key
+
+
+def test_tiny_variant_with_320_tokens():
+    t = wl.config1_tiny(leaf_len=16)
+    Q, K, V = wl.make_qkv(t)
+    got, _ = run_gpu(t, Q, K, V)
+    check(got, reference(t, Q, K, V), strict=True)
+
+
+@pytest.mark.parametrize("cfg,chunk", [(2, 32), (2, 512), (3, 32), (3, 4096), (4, 1024), (5, 2048)])
+def test_other_chunk_sizes(cfg, chunk):
+    # the result does not depend on S_t (the paper's chunk-size ablation only moves latency)
+    t = wl.make_config(cfg)
+    print(f"\n  config {cfg} chunk {chunk}", flush=True)
+    Q, K, V = wl.make_qkv(t)
+    got, _ = run_gpu(t, Q, K, V, chunk_size=chunk)
+    check(got, reference(t, Q, K, V), strict=True)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_forests(seed):
+    # ragged node lengths, zero-length and unreached nodes, repeated / inner-node queries, shuffled and
+    # gapped cache, forests; sizes span several 32-token blocks, several chunks and a ragged tail
+    shapes = [(4, 4, 64), (8, 2, 128), (32, 8, 128), (6, 1, 128), (2, 2, 64), (12, 4, 128)]
+    Hq, Hkv, d = shapes[seed % len(shapes)]
+    t = wl.random_tree(seed, n_nodes=2 + seed % 19, max_len=40 + 17 * (seed % 7), nq=1 + (seed * 3) % 29,
+                       Hq=Hq, Hkv=Hkv, d=d, n_roots=1 + seed % 3)
+    print(f"\n  seed {seed}: nodes={t.n_nodes} ntok={t.ntok} nq={t.nq} Hq={Hq} Hkv={Hkv} d={d}", flush=True)
+    Q, K, V = wl.make_qkv(t)
+    ref = reference(t, Q, K, V)
+    for chunk in (32, 128):
+        got, _ = run_gpu(t, Q, K, V, chunk_size=chunk, out_dtype=torch.float32)
+        check(got, ref, strict=False)
+    got, _ = run_gpu(t, Q, K, V, chunk_size=64)
+    check(got, ref, strict=False)
+
+
+def test_wide_groups_and_many_row_tiles():
+    # 150 queries x 4 query heads per KV head = 600 rows on the shared root: 38 row tiles, ten waves per chunk
+    t = wl._finish("star", [300] + [5] * 150, [-1] + [0] * 150, list(range(1, 151)), 8, 2, 128, 77)
+    Q, K, V = wl.make_qkv(t)
+    got, _ = run_gpu(t, Q, K, V, out_dtype=torch.float32)
+    check(got, reference(t, Q, K, V), strict=False)
+
+
+def test_explicit_scale_and_empty_paths():
+    t = wl.random_tree(3, n_nodes=6, max_len=50, nq=5, Hq=4, Hkv=2, d=128)
+    Q, K, V = wl.make_qkv(t)
+    got, _ = run_gpu(t, Q, K, V, out_dtype=torch.float32, scale=0.31)
+    check(got, reference(t, Q, K, V, scale=0.31), strict=False)
+    # queries whose path has no token: zeros, and no kernel reads K/V
+    t2 = wl._finish("empty", [0, 0, 7], [-1, 0, -1], [1, 1, 2], 4, 2, 64, 5, begins=[0, 0, 0], ntok=7)
+    Q, K, V = wl.make_qkv(t2)
+    got, _ = run_gpu(t2, Q, K, V, out_dtype=torch.float32)
+    assert np.all(got[:2] == 0)
+    check(got, reference(t2, Q, K, V), strict=False)
+    # no queries at all
+    t3 = wl._finish("noq", [9], [-1], [], 4, 2, 64, 5)
+    Q, K, V = wl.make_qkv(t3)
+    got, _ = run_gpu(t3, Q, K, V)
+    assert got.shape == (0, 4, 64)
+
+
+def test_repeated_calls_and_plan_reuse_are_deterministic():
+    t = wl.make_config(1)
+    Q, K, V = wl.make_qkv(t)
+    dev = torch.device("cuda:0")
+    plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok)
+    q, k, v = Q.to(dev), K.to(dev), V.to(dev)
+    a = binding.deft_tree_attn_decode(plan, q, k, v).clone()
+    for _ in range(3):
+        b = binding.deft_tree_attn_decode(plan, q, k, v)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    # a side stream works too
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        c = binding.deft_tree_attn_decode(plan, q, k, v, stream=s)
+    s.synchronize()
+    assert torch.equal(a, c)
+
+
+def test_error_paths_do_not_launch():
+    t = wl.make_config(1)
+    Q, K, V = wl.make_qkv(t)
+    dev = torch.device("cuda:0")
+    plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok)
+    q, k, v = Q.to(dev), K.to(dev), V.to(dev)
+    with pytest.raises(binding.DeftError):   # cache shorter than the plan's rows
+        binding.deft_tree_attn_decode(plan, q, k[:100].contiguous(), v[:100].contiguous())
+    with pytest.raises(binding.DeftError):   # CPU tensors: there is no CPU path
+        binding.deft_tree_attn_decode(plan, Q, K, V)
+    small = torch.empty(64, dtype=torch.uint8, device=dev)
+    with pytest.raises(binding.DeftError) as e:
+        binding.deft_tree_attn_decode(plan, q, k, v, workspace=small)
+    assert e.value.status == -3
+    lib = binding.load_library()
+    o = torch.empty_like(q)
+    ws = plan.workspace(4, 4, 64, dev)
+    # decode before any image exists for this head ratio
+    plan2 = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok)
+    rc = lib.deft_tree_attn_decode(plan2.handle, ws.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                   o.data_ptr(), 4, 4, 64, 0.0, 0, ws.data_ptr(), ws.numel(), None)
+    assert rc == -5
+    rc = lib.deft_tree_attn_decode(plan.handle, plan.image(4, 4, dev).data_ptr(), q.data_ptr(), k.data_ptr(),
+                                   v.data_ptr(), o.data_ptr(), 4, 4, 96, 0.0, 0, ws.data_ptr(), ws.numel(), None)
+    assert rc == -1
+    torch.cuda.synchronize()
