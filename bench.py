@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-attention decode hot path on one MI355X.
+
+A step is one decode iteration over a model of `--layers` attention layers that all see the same
+decoding tree: the QKV preparation (deft_plan on the host + upload of its device image) once, then one
+tree-attention layer-call (stage 1 partial attention + stage 2 global reduction) per layer, each
+layer on its own K/V cache and queries, all resident in HBM before the clock starts.  Distinct
+caches per layer are what a real model has, and they keep every layer-call cold with respect to
+the 256 MB memory-side cache.
+
+Prints ONE JSON line: the metric is microseconds per layer-call (whole step divided by the number
+of layers, so the plan's cost is included pro rata), plus
+  roofline     stage-1 kernel: algorithmic KV bytes per launch / mean launch duration (HIP events on
+               the launch stream, taken in a second pass over the same work) against the 8 TB/s peak
+  cpu_baseline the fp64 oracle timed on this machine's host cores for one layer-call of the same workload
+"""
+
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = few-shot, the headline)")
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--chunk", type=int, default=0, help="S_t, tokens per chunk (0 = library default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="bound on the oracle timing loop")
+    return ap.parse_args()
+
+
+def traffic_from_profiles(workload: str):
+    """HBM bytes per stage-1 launch measured with rocprofv3 --pmc, if a committed summary states it."""
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"\s*TRAFFIC_BYTES_PER_LAUNCH\s+(\S+)\s*=\s*([0-9.eE+]+)", line)
+        if m and m.group(1) == workload:
+            return float(m.group(2))
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collective path exists); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2404_00242_amd import binding, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    lib = binding.load_library()
+
+    tree = workloads.make_config(args.config)
+    Hq, Hkv, d, L = tree.Hq, tree.Hkv, tree.d, args.layers
+    Q0, K0, V0 = workloads.make_qkv(tree)  # layer 0: the seeded workload the parity tests use
+
+    # per-layer inputs, resident in HBM
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(tree.value_seed)
+    qs, ks, vs, outs = [Q0.to(dev)], [K0.to(dev)], [V0.to(dev)], []
+    for _ in range(1, L):
+        qs.append(torch.randn((tree.nq, Hq, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
+        ks.append(torch.randn((tree.ntok, Hkv, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
+        vs.append(torch.randn((tree.ntok, Hkv, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
+    for _ in range(L):
+        outs.append(torch.empty((tree.nq, Hq, d), device=dev, dtype=torch.bfloat16))
+
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    nb = np.ascontiguousarray(tree.node_tok_begin, dtype=np.int32)
+    nl = np.ascontiguousarray(tree.node_tok_len, dtype=np.int32)
+    par = np.ascontiguousarray(tree.node_parent, dtype=np.int32)
+    qn = np.ascontiguousarray(tree.query_node, dtype=np.int32)
+    nbp, nlp, parp, qnp = (a.ctypes.data_as(i32p) for a in (nb, nl, par, qn))
+
+    # sizes are a property of the tree: allocate the image buffer and the workspace once
+    probe = binding.deft_plan(nb, nl, par, qn, tree.ntok, args.chunk)
+    view = probe.view()
+    img_bytes = probe.device_bytes(Hq, Hkv)
+    ws_bytes = probe.workspace_bytes(Hq, Hkv, d)
+    image = torch.empty(img_bytes, dtype=torch.uint8, device=dev)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev)
+    st = ctypes.c_void_p(stream.cuda_stream)
+    vp = ctypes.c_void_p
+    layer_ptrs = [(vp(qs[i].data_ptr()), vp(ks[i].data_ptr()), vp(vs[i].data_ptr()), vp(outs[i].data_ptr()))
+                  for i in range(L)]
+    imgp, wsp = vp(image.data_ptr()), vp(ws.data_ptr())
+
+    def check(rc, what):
+        if rc != 0:
+            raise RuntimeError(f"{what} failed: {lib.deft_strerror(rc).decode()} {lib.deft_last_hip_error().decode()}")
+
+    def prepare():
+        h = vp()
+        check(lib.deft_plan(nbp, nlp, parp, tree.n_nodes, qnp, tree.nq, tree.ntok, args.chunk, 0, ctypes.byref(h)),
+              "deft_plan")
+        if lib.deft_plan_device_bytes(h, Hq, Hkv) > img_bytes:
+            raise RuntimeError("plan image grew")
+        check(lib.deft_plan_upload(h, Hq, Hkv, imgp, img_bytes, st), "deft_plan_upload")
+        return h
+
+    def step():
+        h = prepare()
+        for (qp, kp, vpp, op) in layer_ptrs:
+            rc = lib.deft_tree_attn_decode(h, imgp, qp, kp, vpp, op, Hq, Hkv, d, 0.0, 0, wsp, ws_bytes, st)
+            if rc != 0:
+                check(rc, "deft_tree_attn_decode")
+        return h
+
+    plans = []
+    for _ in range(args.warmup):
+        plans.append(step())
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plans.append(step())
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    step_s = (t1 - t0) / max(args.steps, 1)
+    us_per_call = step_s * 1e6 / L
+
+    # host cost of the preparation phase alone
+    tp0 = time.perf_counter()
+    for _ in range(10):
+        plans.append(prepare())
+    plan_us = (time.perf_counter() - tp0) * 1e5
+
+    # second pass: per-stage durations with events on the launch stream
+    h = plans[-1]
+    n_prof = max(args.steps, 1)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_prof * L)]
+    torch.cuda.synchronize()
+    i = 0
+    for _ in range(n_prof):
+        for (qp, kp, vpp, op) in layer_ptrs:
+            e0, e1, e2 = ev[i]
+            i += 1
+            e0.record(stream)
+            lib.deft_stage1_partial_attention(h, imgp, qp, kp, vpp, Hq, Hkv, d, 0.0, wsp, ws_bytes, st)
+            e1.record(stream)
+            lib.deft_stage2_global_reduction(h, imgp, op, Hq, Hkv, d, 0.0, 0, wsp, ws_bytes, st)
+            e2.record(stream)
+    torch.cuda.synchronize()
+    s1_us = float(np.mean([e[0].elapsed_time(e[1]) for e in ev])) * 1e3
+    s2_us = float(np.mean([e[1].elapsed_time(e[2]) for e in ev])) * 1e3
+
+    kv_bytes = view["n_flat"] * Hkv * 2 * d * 2  # K and V of every reached token, once per KV head
+    achieved = kv_bytes / (s1_us * 1e-6) / 1e9
+    workload = tree.name
+
+    result = {
+        "metric": "tree_attn_decode_us_per_layer_call",
+        "value": round(us_per_call, 3),
+        "unit": "us/layer-call",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(step_s * 1e3, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": workload, "Hq": Hq, "Hkv": Hkv, "d": d, "ntok": tree.ntok, "nq": tree.nq,
+            "layers_per_step": L, "chunk_size": view["chunk_size"], "n_chunks": view["n_chunks"],
+            "n_slots": view["n_slots"], "path_tokens": workloads.path_token_count(tree),
+        },
+        "kv_gbs_whole_call": round(kv_bytes / (us_per_call * 1e-6) / 1e9, 1),
+        "kv_frac_of_peak_whole_call": round(kv_bytes / (us_per_call * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+        "stage1_us": round(s1_us, 3),
+        "stage2_us": round(s2_us, 3),
+        "plan_plus_upload_us": round(plan_us, 1),
+        "roofline": {
+            "kernel": "deft_stage1 (partial attention, one layer-call)",
+            "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": kv_bytes,
+            "traffic": traffic_from_profiles(workload),
+        },
+    }
+
+    # parity of layer 0 and the CPU baseline: the oracle as it stands, on this machine's host cores
+    if not args.no_cpu_baseline:
+        import oracle
+
+        reps, used, ref = 0, 0, None
+        tc0 = time.perf_counter()
+        while True:
+            ref, used = oracle.tree_attention(Q0, K0, V0, nb, nl, par, qn, return_threads=True)
+            reps += 1
+            if time.perf_counter() - tc0 >= args.cpu_seconds:
+                break
+        cpu_us = (time.perf_counter() - tc0) / reps * 1e6
+        got = outs[0].float().cpu().numpy().astype(np.float64)
+        err = float(np.abs(got - ref).max())
+        result["cpu_baseline"] = {
+            "value": round(cpu_us, 1), "unit": "us/layer-call", "cores": used, "kind": "oracle",
+            "sample": f"one full layer-call of {workload} (fp64, all {tree.nq}x{Hq} query rows), mean of {reps} runs",
+        }
+        result["parity_layer0"] = {"max_abs_err": err, "ok": bool(err <= 2e-3)}
+
+    for h in plans:
+        lib.deft_plan_destroy(h)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

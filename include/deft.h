@@ -164,6 +164,25 @@ int deft_tree_attn_decode(const deft_plan_t *plan, const void *dev_image, const 
                           const void *v, void *o, int32_t Hq, int32_t Hkv, int32_t d, float scale,
                           uint32_t flags, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The two stages of Algorithm 4 as separate calls, for callers that want to time or overlap them.
+ * deft_tree_attn_decode(...) is exactly stage 1 followed by stage 2 on the same stream with the
+ * same workspace and scale.  Arguments, alignment rules and errors are those of
+ * deft_tree_attn_decode.
+ *   stage 1: per QKV group, masked partial attention with an online softmax; writes, for every
+ *            (slot, query head), the running maximum m of the raw scores q.k, the sum l of
+ *            exp(scale*(s - m)) and the un-normalised sum acc of exp(scale*(s - m)) * v into the
+ *            workspace (LSE = scale*m + log l and PA = acc / l in the paper's notation).
+ *   stage 2: per (query, query head), the global reduction of eq. 1 over the query's slots;
+ *            reads the workspace, writes o.
+ */
+int deft_stage1_partial_attention(const deft_plan_t *plan, const void *dev_image, const void *q, const void *k,
+                                  const void *v, int32_t Hq, int32_t Hkv, int32_t d, float scale, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+int deft_stage2_global_reduction(const deft_plan_t *plan, const void *dev_image, void *o, int32_t Hq, int32_t Hkv,
+                                 int32_t d, float scale, uint32_t flags, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
 void deft_plan_destroy(deft_plan_t *plan);
 
 const char *deft_strerror(int status);

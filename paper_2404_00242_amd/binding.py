@@ -21,7 +21,8 @@ DEFT_OUT_F32 = 1
 
 EXPORTS = (
     "deft_plan", "deft_plan_view", "deft_plan_device_bytes", "deft_plan_upload", "deft_workspace_bytes",
-    "deft_tree_attn_decode", "deft_plan_destroy", "deft_strerror", "deft_last_hip_error",
+    "deft_tree_attn_decode", "deft_stage1_partial_attention", "deft_stage2_global_reduction",
+    "deft_plan_destroy", "deft_strerror", "deft_last_hip_error",
 )
 
 _i32p = ctypes.POINTER(ctypes.c_int32)
@@ -87,6 +88,11 @@ def load_library():
     lib.deft_tree_attn_decode.restype = ctypes.c_int
     lib.deft_tree_attn_decode.argtypes = [vp, vp, vp, vp, vp, vp, c32, c32, c32, ctypes.c_float, ctypes.c_uint32,
                                           vp, csz, vp]
+    lib.deft_stage1_partial_attention.restype = ctypes.c_int
+    lib.deft_stage1_partial_attention.argtypes = [vp, vp, vp, vp, vp, c32, c32, c32, ctypes.c_float, vp, csz, vp]
+    lib.deft_stage2_global_reduction.restype = ctypes.c_int
+    lib.deft_stage2_global_reduction.argtypes = [vp, vp, vp, c32, c32, c32, ctypes.c_float, ctypes.c_uint32, vp, csz,
+                                                 vp]
     lib.deft_plan_destroy.restype = None
     lib.deft_plan_destroy.argtypes = [vp]
     lib.deft_strerror.restype = ctypes.c_char_p

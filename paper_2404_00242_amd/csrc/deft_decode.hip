@@ -332,7 +332,7 @@ bool launch_stage1(const Stage1Args &args, hipStream_t stream) {
 }
 
 template <int D>
-bool launch_all(const deft::Schedule &S, Stage1Args a1, const Stage2Args &a2, const uint8_t *image, hipStream_t stream) {
+bool launch_stage1_lists(const deft::Schedule &S, Stage1Args a1, const uint8_t *image, hipStream_t stream) {
     for (const deft::ItemList &L : S.lists) {
         a1.items = reinterpret_cast<const int32_t *>(image + L.offset);
         a1.n_items = L.n_items;
@@ -345,11 +345,101 @@ bool launch_all(const deft::Schedule &S, Stage1Args a1, const Stage2Args &a2, co
         }
         if (!ok) return false;
     }
-    if (a2.nq > 0) {
-        hipLaunchKernelGGL((deft_stage2<D>), dim3((unsigned)a2.nq * (unsigned)a2.Hq), dim3(64), 0, stream, a2);
-        if (!hip_ok(hipGetLastError(), "deft_stage2 launch")) return false;
-    }
     return true;
+}
+
+template <int D>
+bool launch_stage2(const Stage2Args &a2, hipStream_t stream) {
+    if (a2.nq == 0) return true;
+    hipLaunchKernelGGL((deft_stage2<D>), dim3((unsigned)a2.nq * (unsigned)a2.Hq), dim3(64), 0, stream, a2);
+    return hip_ok(hipGetLastError(), "deft_stage2 launch");
+}
+
+// Everything the two stages share: argument checks, the schedule, the workspace carve-up.
+struct Call {
+    const deft::Schedule *S = nullptr;
+    const uint8_t *img = nullptr;
+    float *acc = nullptr, *pm = nullptr, *pl = nullptr;
+    float c = 0.f;
+    hipStream_t stream = nullptr;
+};
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+int prepare(const deft_plan_t *plan, const void *dev_image, int32_t Hq, int32_t Hkv, int32_t d, float scale,
+            void *workspace, size_t workspace_bytes, void *stream, Call &call) {
+    if (!plan || !dev_image || !workspace) return DEFT_EINVAL;
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || (d != 64 && d != 128)) return DEFT_EINVAL;
+    if (!aligned16(workspace) || !aligned16(dev_image)) return DEFT_EINVAL;
+    call.S = deft::find_schedule(plan, Hq / Hkv);
+    if (!call.S) return DEFT_ENOTREADY;
+    if (workspace_bytes < deft_workspace_bytes(plan, Hq, Hkv, d)) return DEFT_EWORKSPACE;
+    for (const deft::ItemList &L : call.S->lists)
+        if ((int64_t)L.n_items * Hkv > INT32_MAX) return DEFT_EINVAL;  // grid sizes are 32-bit
+    if ((int64_t)plan->nq * Hq > INT32_MAX) return DEFT_EINVAL;
+    const size_t rows = (size_t)plan->n_slots() * (size_t)Hq;
+    call.img = static_cast<const uint8_t *>(dev_image);
+    call.acc = static_cast<float *>(workspace);
+    call.pm = call.acc + rows * (size_t)d;
+    call.pl = call.pm + rows;
+    if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)d);
+    call.c = scale * 1.4426950408889634f;  // log2(e)
+    call.stream = reinterpret_cast<hipStream_t>(stream);
+    return DEFT_OK;
+}
+
+int run_stage1(const deft_plan_t *plan, const Call &call, const void *q, const void *k, const void *v, int32_t Hq,
+               int32_t Hkv, int32_t d) {
+    if (plan->n_chunks() == 0) return DEFT_OK;
+    if (!q || !k || !v || !aligned16(q) || !aligned16(k) || !aligned16(v)) return DEFT_EINVAL;
+    const deft::Schedule &S = *call.S;
+    auto at = [&](size_t off) { return reinterpret_cast<const int32_t *>(call.img + off); };
+    Stage1Args a1{};
+    a1.q = static_cast<const uint16_t *>(q);
+    a1.k = static_cast<const uint16_t *>(k);
+    a1.v = static_cast<const uint16_t *>(v);
+    a1.part_acc = call.acc;
+    a1.part_m = call.pm;
+    a1.part_l = call.pl;
+    a1.chunk_seg_ptr = at(S.off_chunk_seg_ptr);
+    a1.seg_tok_begin = at(S.off_seg_tok_begin);
+    a1.seg_len = at(S.off_seg_len);
+    a1.seg_qlo = at(S.off_seg_qlo);
+    a1.seg_qhi = at(S.off_seg_qhi);
+    a1.chunk_qlo = at(S.off_chunk_qlo);
+    a1.chunk_qhi = at(S.off_chunk_qhi);
+    a1.chunk_slot_base = at(S.off_chunk_slot_base);
+    a1.q_order = at(S.off_q_order);
+    a1.Hq = Hq;
+    a1.Hkv = Hkv;
+    a1.G = Hq / Hkv;
+    a1.chunk_size = plan->chunk_size;
+    a1.c = call.c;
+    const bool ok = d == 128 ? launch_stage1_lists<128>(S, a1, call.img, call.stream)
+                             : launch_stage1_lists<64>(S, a1, call.img, call.stream);
+    return ok ? DEFT_OK : DEFT_EHIP;
+}
+
+int run_stage2(const deft_plan_t *plan, const Call &call, void *o, int32_t Hq, int32_t d, uint32_t flags) {
+    if (flags != DEFT_OUT_BF16 && flags != DEFT_OUT_F32) return DEFT_EINVAL;
+    if (plan->nq == 0) return DEFT_OK;
+    if (!o || (reinterpret_cast<uintptr_t>(o) & 3)) return DEFT_EINVAL;
+    const deft::Schedule &S = *call.S;
+    auto at = [&](size_t off) { return reinterpret_cast<const int32_t *>(call.img + off); };
+    Stage2Args a2{};
+    a2.part_acc = call.acc;
+    a2.part_m = call.pm;
+    a2.part_l = call.pl;
+    a2.q_order = at(S.off_q_order);
+    a2.q_part_ptr = at(S.off_q_part_ptr);
+    a2.q_part_slot = at(S.off_q_part_slot);
+    a2.out = o;
+    a2.nq = plan->nq;
+    a2.Hq = Hq;
+    a2.out_f32 = (flags == DEFT_OUT_F32);
+    a2.c = call.c;
+    const bool ok = d == 128 ? launch_stage2<128>(a2, call.stream) : launch_stage2<64>(a2, call.stream);
+    return ok ? DEFT_OK : DEFT_EHIP;
 }
 
 }  // namespace
@@ -358,7 +448,7 @@ extern "C" const char *deft_last_hip_error(void) { return g_hip_error.c_str(); }
 
 extern "C" int deft_plan_upload(deft_plan_t *plan, int32_t Hq, int32_t Hkv, void *dev_image, size_t bytes, void *stream) {
     if (!plan || !dev_image || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return DEFT_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(dev_image) & 15) != 0) return DEFT_EINVAL;
+    if (!aligned16(dev_image)) return DEFT_EINVAL;
     const deft::Schedule *S = nullptr;
     try {
         S = deft::get_schedule(plan, Hq / Hkv);
@@ -373,71 +463,34 @@ extern "C" int deft_plan_upload(deft_plan_t *plan, int32_t Hq, int32_t Hkv, void
     return DEFT_OK;
 }
 
+extern "C" int deft_stage1_partial_attention(const deft_plan_t *plan, const void *dev_image, const void *q,
+                                             const void *k, const void *v, int32_t Hq, int32_t Hkv, int32_t d,
+                                             float scale, void *workspace, size_t workspace_bytes, void *stream) {
+    Call call;
+    int rc = prepare(plan, dev_image, Hq, Hkv, d, scale, workspace, workspace_bytes, stream, call);
+    if (rc != DEFT_OK) return rc;
+    return run_stage1(plan, call, q, k, v, Hq, Hkv, d);
+}
+
+extern "C" int deft_stage2_global_reduction(const deft_plan_t *plan, const void *dev_image, void *o, int32_t Hq,
+                                            int32_t Hkv, int32_t d, float scale, uint32_t flags, void *workspace,
+                                            size_t workspace_bytes, void *stream) {
+    Call call;
+    int rc = prepare(plan, dev_image, Hq, Hkv, d, scale, workspace, workspace_bytes, stream, call);
+    if (rc != DEFT_OK) return rc;
+    return run_stage2(plan, call, o, Hq, d, flags);
+}
+
 extern "C" int deft_tree_attn_decode(const deft_plan_t *plan, const void *dev_image, const void *q, const void *k,
                                      const void *v, void *o, int32_t Hq, int32_t Hkv, int32_t d, float scale,
                                      uint32_t flags, void *workspace, size_t workspace_bytes, void *stream) {
-    if (!plan || !dev_image || !workspace) return DEFT_EINVAL;
-    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || (d != 64 && d != 128)) return DEFT_EINVAL;
+    Call call;
+    int rc = prepare(plan, dev_image, Hq, Hkv, d, scale, workspace, workspace_bytes, stream, call);
+    if (rc != DEFT_OK) return rc;
+    // check both stages' arguments before launching anything
     if (flags != DEFT_OUT_BF16 && flags != DEFT_OUT_F32) return DEFT_EINVAL;
-    if (plan->nq > 0 && (!q || !o)) return DEFT_EINVAL;  // with no queries Q and O are empty and may be null
-    if (plan->n_chunks() > 0 && (!k || !v)) return DEFT_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(workspace) & 15) || (reinterpret_cast<uintptr_t>(dev_image) & 15) ||
-        (reinterpret_cast<uintptr_t>(q) & 15) || (reinterpret_cast<uintptr_t>(k) & 15) ||
-        (reinterpret_cast<uintptr_t>(v) & 15) || (reinterpret_cast<uintptr_t>(o) & 3))
-        return DEFT_EINVAL;
-    const deft::Schedule *S = deft::find_schedule(plan, Hq / Hkv);
-    if (!S) return DEFT_ENOTREADY;
-    if (workspace_bytes < deft_workspace_bytes(plan, Hq, Hkv, d)) return DEFT_EWORKSPACE;
-    // grid sizes are 32-bit
-    for (const deft::ItemList &L : S->lists)
-        if ((int64_t)L.n_items * Hkv > INT32_MAX) return DEFT_EINVAL;
-    if ((int64_t)plan->nq * Hq > INT32_MAX) return DEFT_EINVAL;
-
-    const uint8_t *img = static_cast<const uint8_t *>(dev_image);
-    auto at = [&](size_t off) { return reinterpret_cast<const int32_t *>(img + off); };
-    const size_t rows = (size_t)plan->n_slots() * (size_t)Hq;
-    float *acc = static_cast<float *>(workspace);
-    float *pm = acc + rows * (size_t)d;
-    float *pl = pm + rows;
-    if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)d);
-    const float c = scale * 1.4426950408889634f;
-
-    Stage1Args a1{};
-    a1.q = static_cast<const uint16_t *>(q);
-    a1.k = static_cast<const uint16_t *>(k);
-    a1.v = static_cast<const uint16_t *>(v);
-    a1.part_acc = acc;
-    a1.part_m = pm;
-    a1.part_l = pl;
-    a1.chunk_seg_ptr = at(S->off_chunk_seg_ptr);
-    a1.seg_tok_begin = at(S->off_seg_tok_begin);
-    a1.seg_len = at(S->off_seg_len);
-    a1.seg_qlo = at(S->off_seg_qlo);
-    a1.seg_qhi = at(S->off_seg_qhi);
-    a1.chunk_qlo = at(S->off_chunk_qlo);
-    a1.chunk_qhi = at(S->off_chunk_qhi);
-    a1.chunk_slot_base = at(S->off_chunk_slot_base);
-    a1.q_order = at(S->off_q_order);
-    a1.Hq = Hq;
-    a1.Hkv = Hkv;
-    a1.G = Hq / Hkv;
-    a1.chunk_size = plan->chunk_size;
-    a1.c = c;
-
-    Stage2Args a2{};
-    a2.part_acc = acc;
-    a2.part_m = pm;
-    a2.part_l = pl;
-    a2.q_order = at(S->off_q_order);
-    a2.q_part_ptr = at(S->off_q_part_ptr);
-    a2.q_part_slot = at(S->off_q_part_slot);
-    a2.out = o;
-    a2.nq = plan->nq;
-    a2.Hq = Hq;
-    a2.out_f32 = (flags == DEFT_OUT_F32);
-    a2.c = c;
-
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const bool ok = d == 128 ? launch_all<128>(*S, a1, a2, img, st) : launch_all<64>(*S, a1, a2, img, st);
-    return ok ? DEFT_OK : DEFT_EHIP;
+    if (plan->nq > 0 && (!o || (reinterpret_cast<uintptr_t>(o) & 3))) return DEFT_EINVAL;
+    rc = run_stage1(plan, call, q, k, v, Hq, Hkv, d);
+    if (rc != DEFT_OK) return rc;
+    return run_stage2(plan, call, o, Hq, d, flags);
 }

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol(repo_root):
     header = open(os.path.join(repo_root, "include", "deft.h")).read()
     import re
 
-    declared = set(re.findall(r"\b(deft_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(deft_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
