@@ -1,8 +1,8 @@
 // Device side of libdeft: the Attention Calculation Phase of DeFT-Flatten (Algorithm 4) for gfx950.
 //
-// Stage 1 (deft_stage1): one wave per work item = (chunk, KV head, range of 16-row tiles).  The
-// rows of a tile are (query of the chunk's group) x (query head reading this KV head).  The wave
-// streams the chunk 32 tokens at a time straight from HBM into MFMA operand registers:
+// Stage 1 (deft_stage1): one workgroup of four waves per task = (chunk, KV head, up to four 16-row
+// tiles).  The rows of a tile are (query of the chunk's group) x (query head reading this KV head).
+// A wave streams 32 tokens at a time straight from HBM into MFMA operand registers:
 //
 //   S^T[token, row] = K[token, :] . Q[row, :]      v_mfma_f32_16x16x32_bf16, A = K tile (a lane holds
 //                                                   8 consecutive d of one token = one 128-bit load),
@@ -12,14 +12,18 @@
 //                                                   16-bit interleave in registers (v_perm_b32),
 //                                                   B = P^T, which is S^T's accumulator layout as is
 //
-// Each token row of one head (2*d bytes, contiguous) is fetched exactly once per work item and every
-// byte of every 64-byte sector requested is used, so nothing is staged through LDS; LDS only holds the
-// chunk's per-token table (physical row, query interval) expanded from the plan's segment table.
+// Each token row of one head (2*d bytes, contiguous) is fetched from HBM exactly once per task and every
+// byte of every 64-byte sector requested is used.  A narrow group (one row tile) splits the chunk's
+// tokens over the four waves, each keeping two blocks of loads in flight in registers.  A wider group
+// gives each wave its own row tile; the waves that need the same block each fetch a share of it and pass
+// the operand registers to the others through LDS.  The waves' partial results are merged in LDS before
+// one (m, l, acc) triple per (chunk, row) is written.
 //
 // Stage 2 (deft_stage2): one wave per (query, query head) merges that query's partial results with
 // the log-sum-exp weights of eq. 1.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -37,9 +41,9 @@ typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
 struct Stage1Args {
     const uint16_t *q, *k, *v;
     float *part_acc, *part_m, *part_l;
-    const int32_t *chunk_seg_ptr, *seg_tok_begin, *seg_len, *seg_qlo, *seg_qhi;
-    const int32_t *chunk_qlo, *chunk_qhi, *chunk_slot_base, *q_order;
-    const int32_t *items;
+    const int32_t *seg_tok_begin, *seg_len, *seg_qlo, *seg_qhi, *seg_off;
+    const int32_t *q_order;
+    const int32_t *items;  // deft::kItemInts int32 per work item, see deft_internal.h
     int32_t n_items, Hq, Hkv, G, chunk_size;
     float c;  // scale * log2(e): probabilities are 2^((s - m) * c)
 };
@@ -55,7 +59,7 @@ struct Stage2Args {
 __device__ __forceinline__ u32x4 load16(const uint16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
 
 __device__ __forceinline__ float wave_row_max(float x) {
-    // rows live in lanes {n, n+16, n+32, n+48}
+    // a row of a 16-row tile lives in lanes {n, n+16, n+32, n+48}
     x = fmaxf(x, __shfl_xor(x, 16));
     x = fmaxf(x, __shfl_xor(x, 32));
     return x;
@@ -72,245 +76,468 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, r);
 }
 
-template <int D, int NT>
-__global__ __launch_bounds__(64) void deft_stage1(Stage1Args a) {
-    constexpr int KK = D / 32;   // k-steps of the Q.K^T contraction
-    constexpr int DT = 8;        // P.V products per block (index c' below): a lane loads 8 d of V per token.
-                                 // With D = 64 lanes n16 >= 8 repeat the loads of n16 - 8 and half of each
-                                 // product is discarded; that shape only occurs in tiny, latency-bound cases.
-    static_assert(D == 64 || D == 128, "head dimension");
+constexpr int kWaves = 4;              // waves per stage-1 workgroup
+constexpr int kXbufBytes = 64 * 1024;  // LDS register-exchange area: 2 token parts x 2 stages x 16 KB
 
-    extern __shared__ int32_t s_tab[];
-    int32_t *s_row = s_tab;
-    int32_t *s_qlo = s_tab + a.chunk_size;
-    int32_t *s_qhi = s_tab + 2 * a.chunk_size;
+// What a wave needs to know about its chunk to address tokens.
+struct ChunkCtx {
+    const uint16_t *kbase, *vbase;  // K/V pointers already offset to this head and this lane's d slice
+    size_t row_stride;              // elements between consecutive token rows
+    const int32_t *s_row, *s_qlo, *s_qhi;  // LDS per-token table (only when !uniform), padded to whole blocks
+    int clen;                       // tokens in the chunk
+    int uniform;                    // the chunk is one piece of one node: rows are begin0 + x
+    int begin0, qlo0, qhi0;
+    int n16, g;
+};
 
-    const int lane = threadIdx.x;
-    const int n16 = lane & 15;
-    const int g = lane >> 4;
-    const int item = blockIdx.x / a.Hkv;
-    const int h = blockIdx.x - item * a.Hkv;
-    const int chunk = a.items[2 * item];
-    const int tile0 = a.items[2 * item + 1] & 0xffffff;
-    const int ntiles = a.items[2 * item + 1] >> 24;
-    const int seg0 = a.chunk_seg_ptr[chunk], seg1 = a.chunk_seg_ptr[chunk + 1];
-    const int cqlo = a.chunk_qlo[chunk];
-    const int R = (a.chunk_qhi[chunk] - cqlo) * a.G;
+// One 32-token block as MFMA operands: K as the A operand of S^T = K Q^T (token 16a + n16, d = 32kk + 8g..+7),
+// V as loaded, row-major (token 16a + 4g + i, d = 8*n16..+7).  The layout is the same in every wave, whatever
+// row tile the wave works on, which is what lets waves exchange these registers through LDS unchanged.
+template <int D>
+struct KVRegs {
+    bf16x8 k[2][D / 32];
+    u32x4 v[8];
+};
 
-    // ---- per-token table of the chunk: physical row and the interval of plan positions that attend
-    int clen = 0;
-    for (int s = seg0; s < seg1; ++s) {
-        const int b = a.seg_tok_begin[s], n = a.seg_len[s], lo = a.seg_qlo[s], hi = a.seg_qhi[s];
-        for (int i = lane; i < n; i += 64) {
-            s_row[clen + i] = b + i;
-            s_qlo[clen + i] = lo;
-            s_qhi[clen + i] = hi;
-        }
-        clen += n;
+// physical row of chunk position x; positions past the chunk's end give a row that exists (their scores are masked)
+__device__ __forceinline__ int tok_row(const ChunkCtx &c, int x) {
+    return c.uniform ? c.begin0 + min(x, c.clen - 1) : c.s_row[x];
+}
+
+template <int D>
+__device__ __forceinline__ void load_block(KVRegs<D> &r, const ChunkCtx &c, int x0) {
+#pragma unroll
+    for (int aa = 0; aa < 2; ++aa) {
+        const uint16_t *kp = c.kbase + (size_t)tok_row(c, x0 + 16 * aa + c.n16) * c.row_stride;
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk) r.k[aa][kk] = __builtin_bit_cast(bf16x8, load16(kp + 32 * kk));
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            r.v[4 * aa + i] = load16(c.vbase + (size_t)tok_row(c, x0 + 16 * aa + 4 * c.g + i) * c.row_stride);
     }
-    const int nblk = (clen + 31) >> 5;
-    {
-        const int pad_row = a.seg_tok_begin[seg0];  // a row that exists; its scores are masked out
-        for (int i = clen + lane; i < nblk * 32; i += 64) {
-            s_row[i] = pad_row;
-            s_qlo[i] = 0;
-            s_qhi[i] = 0;
-        }
-    }
-    __syncthreads();
+}
 
-    // ---- rows of this wave, and Q as the B operand (resident for the whole chunk)
-    int qpos[NT];
-    bf16x8 qreg[NT][KK];
+// Online-softmax step of one wave over one 32-token block, for its 16-row tile.
+template <int D>
+__device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx &c, int x0,
+                                              const bf16x8 (&qreg)[D / 32], const int qpos, float &m_run,
+                                              float &l_run, f32x4 (&oacc)[8], const float cs) {
+    constexpr int KK = D / 32;
+    // S^T = K Q^T : sacc[a][i] is the score of token 16a + 4g + i against row n16
+    f32x4 sacc[2];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int r = 16 * (tile0 + t) + n16;
-        const bool ok = (t < ntiles) && (r < R);
-        const int pl = r / a.G, gh = r - pl * a.G;
-        qpos[t] = ok ? cqlo + pl : -1;
-        u32x4 z = {0, 0, 0, 0};
+    for (int aa = 0; aa < 2; ++aa) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) qreg[t][kk] = __builtin_bit_cast(bf16x8, z);
-        if (ok) {
-            const int j = a.q_order[cqlo + pl];
-            const uint16_t *qp = a.q + ((size_t)j * a.Hq + (size_t)h * a.G + gh) * D + 8 * g;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) qreg[t][kk] = __builtin_bit_cast(bf16x8, load16(qp + 32 * kk));
-        }
+        for (int kk = 0; kk < KK; ++kk)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.k[aa][kk], qreg[kk], acc, 0, 0, 0);
+        sacc[aa] = acc;
     }
 
-    float m_run[NT], l_run[NT];
-    f32x4 oacc[NT][DT];
+    // mask: a token is visible to plan position qpos iff qlo <= qpos < qhi of the node piece it belongs to
+    float mx = -INFINITY;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        m_run[t] = -INFINITY;
-        l_run[t] = 0.f;
-#pragma unroll
-        for (int c = 0; c < DT; ++c) oacc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    const size_t row_stride = (size_t)a.Hkv * D;     // elements between consecutive tokens
-    const uint16_t *kbase = a.k + (size_t)h * D + 8 * g;
-    const uint16_t *vbase = a.v + (size_t)h * D + 8 * (D == 128 ? n16 : (n16 & 7));
-
-    for (int blk = 0; blk < nblk; ++blk) {
-        const int x0 = blk * 32;
-        // K: token (16a + n16) of the block, d = 32kk + 8g .. +7
-        bf16x8 kreg[2][KK];
-#pragma unroll
-        for (int aa = 0; aa < 2; ++aa) {
-            const uint16_t *kp = kbase + (size_t)s_row[x0 + 16 * aa + n16] * row_stride;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) kreg[aa][kk] = __builtin_bit_cast(bf16x8, load16(kp + 32 * kk));
-        }
-        // V: tokens (16a + 4g + i), d = 8*n16 .. +7; these are also the tokens of this lane's scores
-        u32x4 vraw[8];
-        i32x4 tqlo[2], tqhi[2];
-#pragma unroll
-        for (int aa = 0; aa < 2; ++aa) {
-            const i32x4 rows = *reinterpret_cast<const i32x4 *>(&s_row[x0 + 16 * aa + 4 * g]);
-            tqlo[aa] = *reinterpret_cast<const i32x4 *>(&s_qlo[x0 + 16 * aa + 4 * g]);
-            tqhi[aa] = *reinterpret_cast<const i32x4 *>(&s_qhi[x0 + 16 * aa + 4 * g]);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) vraw[4 * aa + i] = load16(vbase + (size_t)rows[i] * row_stride);
-        }
-
-        // S^T = K Q^T
-        f32x4 sacc[2][NT];
-#pragma unroll
-        for (int aa = 0; aa < 2; ++aa)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kreg[aa][kk], qreg[t][kk], acc, 0, 0, 0);
-                sacc[aa][t] = acc;
-            }
-
-        // V^T operand: 16-bit interleave of token pairs; vt[c'][p] = {V[tok 2p][8*n16 + c'], V[tok 2p+1][..]}
-        u32x4 vt[8];
-#pragma unroll
-        for (int c2 = 0; c2 < 4; ++c2)
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const uint32_t lo = vraw[2 * p][c2], hi = vraw[2 * p + 1][c2];
-                vt[2 * c2][p] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-                vt[2 * c2 + 1][p] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
-            }
-
-        // masked online softmax, one row tile at a time
-        bf16x8 preg[NT];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int aa = 0; aa < 2; ++aa)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const bool on = (qpos[t] >= tqlo[aa][i]) && (qpos[t] < tqhi[aa][i]);
-                    const float s = on ? sacc[aa][t][i] : -INFINITY;
-                    sacc[aa][t][i] = s;
-                    mx = fmaxf(mx, s);
-                }
-            mx = wave_row_max(mx);
-            const float m_new = fmaxf(m_run[t], mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f((m_run[t] - m_use) * a.c);
-            m_run[t] = m_new;
-            const float mc = m_use * a.c;
-            float pv[8];
-            float psum = 0.f;
-#pragma unroll
-            for (int aa = 0; aa < 2; ++aa)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float e = __builtin_amdgcn_exp2f(fmaf(sacc[aa][t][i], a.c, -mc));
-                    pv[4 * aa + i] = e;
-                    psum += e;
-                }
-            l_run[t] = l_run[t] * alpha + psum;
-            u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]),
-                        pack_bf16(pv[6], pv[7])};
-            preg[t] = __builtin_bit_cast(bf16x8, pk);
-#pragma unroll
-            for (int c = 0; c < DT; ++c) oacc[t][c] *= alpha;
-        }
-
-        // O^T += V^T P^T
-#pragma unroll
-        for (int c = 0; c < DT; ++c)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-                oacc[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[c]), preg[t],
-                                                                      oacc[t][c], 0, 0, 0);
-    }
-
-    // ---- partial results: (m, l, un-normalised acc) per (slot, query head)
-    const int slot_base = a.chunk_slot_base[chunk];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const float l_tot = wave_row_sum(l_run[t]);
-        if (qpos[t] < 0) continue;
-        const int r = 16 * (tile0 + t) + n16;
-        const int pl = r / a.G, gh = r - pl * a.G;
-        const size_t ro = (size_t)(slot_base + pl) * a.Hq + (size_t)h * a.G + gh;
-        if (g == 0) {
-            a.part_m[ro] = m_run[t];
-            a.part_l[ro] = l_tot;
-        }
-        // this lane owns d in [32g, 32g+32) of its row: d = 32g + 8i + c'
-        if (D == 128 || g < 2) {
-            float *dst = a.part_acc + ro * D + 32 * g;
+    for (int aa = 0; aa < 2; ++aa) {
+        const int xv = x0 + 16 * aa + 4 * c.g;
+        i32x4 qlo, qhi;
+        if (c.uniform) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                f32x4 lo4 = {oacc[t][0][i], oacc[t][1][i], oacc[t][2][i], oacc[t][3][i]};
-                f32x4 hi4 = {oacc[t][4][i], oacc[t][5][i], oacc[t][6][i], oacc[t][7][i]};
-                *reinterpret_cast<f32x4 *>(dst + 8 * i) = lo4;
-                *reinterpret_cast<f32x4 *>(dst + 8 * i + 4) = hi4;
+                const bool in = xv + i < c.clen;
+                qlo[i] = in ? c.qlo0 : 0;
+                qhi[i] = in ? c.qhi0 : 0;
             }
+        } else {
+            qlo = *reinterpret_cast<const i32x4 *>(&c.s_qlo[xv]);
+            qhi = *reinterpret_cast<const i32x4 *>(&c.s_qhi[xv]);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool on = (qpos >= qlo[i]) && (qpos < qhi[i]);
+            const float sv = on ? sacc[aa][i] : -INFINITY;
+            sacc[aa][i] = sv;
+            mx = fmaxf(mx, sv);
+        }
+    }
+    mx = wave_row_max(mx);
+    const float m_new = fmaxf(m_run, mx);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * cs);
+    m_run = m_new;
+    const float mc = m_use * cs;
+    float pv[8];
+    float psum = 0.f;
+#pragma unroll
+    for (int aa = 0; aa < 2; ++aa)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(sacc[aa][i], cs, -mc));
+            pv[4 * aa + i] = e;
+            psum += e;
+        }
+    l_run = l_run * alpha + psum;
+    const u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]),
+                      pack_bf16(pv[6], pv[7])};
+    const bf16x8 preg = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc) oacc[cc] *= alpha;
+
+    // O^T += V^T P^T.  The V^T operand of product c' = 2*c2 + {0,1} is a 16-bit interleave of token pairs:
+    // vt[p] = {V[tok 2p][8*n16 + c'], V[tok 2p+1][8*n16 + c']}
+#pragma unroll
+    for (int c2 = 0; c2 < 4; ++c2) {
+        u32x4 vt_lo, vt_hi;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t lo = r.v[2 * p][c2], hi = r.v[2 * p + 1][c2];
+            vt_lo[p] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            vt_hi[p] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+        }
+        oacc[2 * c2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt_lo), preg,
+                                                                oacc[2 * c2], 0, 0, 0);
+        oacc[2 * c2 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt_hi), preg,
+                                                                    oacc[2 * c2 + 1], 0, 0, 0);
+    }
+}
+
+// ---- token-split path (groups of one row tile): every wave streams its own blocks, two in flight ----
+template <int D>
+__device__ __forceinline__ void run_split(const ChunkCtx &ctx, int wave, int nblk, const bf16x8 (&qreg)[D / 32],
+                                          int qpos, float &m_run, float &l_run, f32x4 (&oacc)[8], float cs) {
+    // wave w takes blocks w, w+4, w+8, ... (neighbouring waves read neighbouring rows at the same time)
+    KVRegs<D> b0, b1;
+    int blk = wave;
+    if (blk < nblk) load_block<D>(b0, ctx, blk * 32);
+    if (blk + kWaves < nblk) load_block<D>(b1, ctx, (blk + kWaves) * 32);
+    for (; blk < nblk; blk += 2 * kWaves) {
+        compute_block<D>(b0, ctx, blk * 32, qreg, qpos, m_run, l_run, oacc, cs);
+        if (blk + 2 * kWaves < nblk) load_block<D>(b0, ctx, (blk + 2 * kWaves) * 32);
+        if (blk + kWaves < nblk) {
+            compute_block<D>(b1, ctx, (blk + kWaves) * 32, qreg, qpos, m_run, l_run, oacc, cs);
+            if (blk + 3 * kWaves < nblk) load_block<D>(b1, ctx, (blk + 3 * kWaves) * 32);
         }
     }
 }
 
-// Stage 2: tree-topology-aware global reduction (eq. 1 with the running maximum subtracted).
+// ---- row-split path (groups of TR = 2 or 4 row tiles): the TR waves that work on the same blocks each
+//      fetch 1/TR of a block from HBM and pass it to the others through LDS, so the block is read once ----
+template <int D, int TR>
+struct Share {
+    static constexpr int KK = D / 32;
+    static constexpr int H = TR / 2;       // waves per 16-token half of a block
+    static constexpr int NK = KK / H;      // 128-bit K loads of one wave per block
+    static constexpr int NV = 4 / H;       // 128-bit V loads of one wave per block
+    static constexpr int NSLOT = 2 * KK + 8;  // 1 KB register images per block (K then V)
+    u32x4 x[NK + NV];
+};
+
+template <int D, int TR>
+__device__ __forceinline__ void share_issue(Share<D, TR> &s, const ChunkCtx &c, int t, int x0) {
+    using S = Share<D, TR>;
+    const int am = t / S::H, hk = t % S::H;
+    const uint16_t *kp = c.kbase + (size_t)tok_row(c, x0 + 16 * am + c.n16) * c.row_stride;
+#pragma unroll
+    for (int q = 0; q < S::NK; ++q) s.x[q] = load16(kp + 32 * (hk * S::NK + q));
+#pragma unroll
+    for (int q = 0; q < S::NV; ++q)
+        s.x[S::NK + q] = load16(c.vbase + (size_t)tok_row(c, x0 + 16 * am + 4 * c.g + hk * S::NV + q) * c.row_stride);
+}
+
+template <int D, int TR>
+__device__ __forceinline__ void share_step(Share<D, TR> &s, const ChunkCtx &c, u32x4 *xs, int t, int lane, int blk,
+                                           int next_blk, int nblk, const bf16x8 (&qreg)[D / 32], int qpos,
+                                           float &m_run, float &l_run, f32x4 (&oacc)[8], float cs) {
+    using S = Share<D, TR>;
+    constexpr int KK = D / 32;
+    const int am = t / S::H, hk = t % S::H;
+    const bool live = blk < nblk;
+    if (live) {
+#pragma unroll
+        for (int q = 0; q < S::NK; ++q) xs[(am * KK + hk * S::NK + q) * 64 + lane] = s.x[q];
+#pragma unroll
+        for (int q = 0; q < S::NV; ++q) xs[(2 * KK + 4 * am + hk * S::NV + q) * 64 + lane] = s.x[S::NK + q];
+    }
+    __syncthreads();
+    if (next_blk < nblk) share_issue<D, TR>(s, c, t, next_blk * 32);
+    if (live) {
+        KVRegs<D> r;
+#pragma unroll
+        for (int aa = 0; aa < 2; ++aa)
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) r.k[aa][kk] = __builtin_bit_cast(bf16x8, xs[(aa * KK + kk) * 64 + lane]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r.v[j] = xs[(2 * KK + j) * 64 + lane];
+        compute_block<D>(r, c, blk * 32, qreg, qpos, m_run, l_run, oacc, cs);
+    }
+}
+
+template <int D, int TR>
+__device__ __forceinline__ void run_shared(const ChunkCtx &ctx, u32x4 *xbuf, int wave, int lane, int nblk,
+                                           const bf16x8 (&qreg)[D / 32], int qpos, float &m_run, float &l_run,
+                                           f32x4 (&oacc)[8], float cs) {
+    using S = Share<D, TR>;
+    constexpr int NP = kWaves / TR;  // token parts: part p takes blocks p, p+NP, ...
+    const int t = wave % TR, part = wave / TR;
+    const int iters = (nblk + NP - 1) / NP;  // the same for every wave: barriers stay aligned
+    u32x4 *xb = xbuf + (size_t)part * 2 * S::NSLOT * 64;
+    Share<D, TR> sa, sb;
+    int blk = part;
+    if (blk < nblk) share_issue<D, TR>(sa, ctx, t, blk * 32);
+    if (blk + NP < nblk) share_issue<D, TR>(sb, ctx, t, (blk + NP) * 32);
+    for (int it = 0; it < iters; it += 2, blk += 2 * NP) {
+        share_step<D, TR>(sa, ctx, xb, t, lane, blk, blk + 2 * NP, nblk, qreg, qpos, m_run, l_run, oacc, cs);
+        if (it + 1 < iters)
+            share_step<D, TR>(sb, ctx, xb + S::NSLOT * 64, t, lane, blk + NP, blk + 3 * NP, nblk, qreg, qpos, m_run,
+                              l_run, oacc, cs);
+    }
+}
+
+// Stage 1: one workgroup of four waves per task = (chunk, KV head, up to 64 rows of the chunk's group).
+// The rows are (query of the group) x (query head reading this KV head), tiled 16 at a time.  A task with
+// TR row tiles gives wave w tile w % TR and token part w / TR; the parts' partial results are merged in
+// LDS, so one (m, l, acc) triple per (chunk, row) reaches the workspace.
+template <int D>
+__global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
+    constexpr int KK = D / 32;  // k-steps of the Q.K^T contraction
+    // The P.V product runs as 8 MFMAs per block (a lane loads 8 d of V per token).  With D = 64 lanes
+    // n16 >= 8 repeat the loads of n16 - 8 and half of each product is discarded; that shape only occurs
+    // in tiny, latency-bound cases.
+    static_assert(D == 64 || D == 128, "head dimension");
+    constexpr int OP = D + 4;  // padded row pitch (floats) of the merge buffer
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
+    u32x4 *xbuf = reinterpret_cast<u32x4 *>(s_raw);                     // register exchange, kXbufBytes
+    float *mO = reinterpret_cast<float *>(s_raw);                       // merge buffer, aliases the exchange
+    float *mM = mO + kWaves * 16 * OP;
+    float *mL = mM + kWaves * 16;
+    int32_t *s_row = reinterpret_cast<int32_t *>(s_raw + kXbufBytes);   // per-token table
+    int32_t *s_qlo = s_row + a.chunk_size;
+    int32_t *s_qhi = s_qlo + a.chunk_size;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int n16 = lane & 15;
+    const int g = lane >> 4;
+    const int item = blockIdx.x / a.Hkv;
+    const int h = blockIdx.x - item * a.Hkv;
+    const int32_t *it = a.items + (size_t)item * deft::kItemInts;
+    const int tile0 = it[deft::kItTile0], ntiles = it[deft::kItNTiles];
+    const int seg0 = it[deft::kItSeg0], nseg = it[deft::kItNSeg];
+    const int cqlo = it[deft::kItQlo];
+    const int R = it[deft::kItWidth] * a.G;
+    const int slot_base = it[deft::kItSlotBase];
+    const int clen = it[deft::kItLen];
+    const int TR = ntiles <= 1 ? 1 : (ntiles == 2 ? 2 : 4);
+
+    ChunkCtx ctx;
+    ctx.row_stride = (size_t)a.Hkv * D;
+    ctx.kbase = a.k + (size_t)h * D + 8 * g;
+    ctx.vbase = a.v + (size_t)h * D + 8 * (D == 128 ? n16 : (n16 & 7));
+    ctx.s_row = s_row;
+    ctx.s_qlo = s_qlo;
+    ctx.s_qhi = s_qhi;
+    ctx.clen = clen;
+    ctx.uniform = (nseg == 1);
+    ctx.begin0 = it[deft::kItBegin0];
+    ctx.qlo0 = it[deft::kItSegQlo0];
+    ctx.qhi0 = it[deft::kItSegQhi0];
+    ctx.n16 = n16;
+    ctx.g = g;
+    const int nblk = (clen + 31) >> 5;
+
+    // ---- chunks made of several node pieces: per-token table (physical row, interval of plan
+    //      positions that attend) expanded from the plan's segment table into LDS
+    if (nseg > 1) {
+        if (nseg <= 16) {
+            for (int s = seg0; s < seg0 + nseg; ++s) {
+                const int b = a.seg_tok_begin[s], n = a.seg_len[s], lo = a.seg_qlo[s], hi = a.seg_qhi[s];
+                const int off = a.seg_off[s];
+                for (int i = tid; i < n; i += 64 * kWaves) {
+                    s_row[off + i] = b + i;
+                    s_qlo[off + i] = lo;
+                    s_qhi[off + i] = hi;
+                }
+            }
+        } else {
+            for (int s = seg0 + tid; s < seg0 + nseg; s += 64 * kWaves) {
+                const int b = a.seg_tok_begin[s], n = a.seg_len[s], lo = a.seg_qlo[s], hi = a.seg_qhi[s];
+                const int off = a.seg_off[s];
+                for (int i = 0; i < n; ++i) {
+                    s_row[off + i] = b + i;
+                    s_qlo[off + i] = lo;
+                    s_qhi[off + i] = hi;
+                }
+            }
+        }
+        for (int i = clen + tid; i < nblk * 32; i += 64 * kWaves) {  // last block's padding: a real row, masked
+            s_row[i] = ctx.begin0;
+            s_qlo[i] = 0;
+            s_qhi[i] = 0;
+        }
+        __syncthreads();
+    }
+
+    // ---- this wave's 16 rows, and Q as the B operand (resident for the whole chunk)
+    const int my_tile = wave % TR;
+    int qpos = -1;
+    bf16x8 qreg[KK];
+    {
+        const int r = 16 * (tile0 + my_tile) + n16;
+        const bool ok = (my_tile < ntiles) && (r < R);
+        const int pl = r / a.G, gh = r - pl * a.G;
+        const u32x4 z = {0, 0, 0, 0};
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) qreg[kk] = __builtin_bit_cast(bf16x8, z);
+        if (ok) {
+            qpos = cqlo + pl;
+            const int j = a.q_order[cqlo + pl];
+            const uint16_t *qp = a.q + ((size_t)j * a.Hq + (size_t)h * a.G + gh) * D + 8 * g;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) qreg[kk] = __builtin_bit_cast(bf16x8, load16(qp + 32 * kk));
+        }
+    }
+
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x4 oacc[8];
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc) oacc[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (TR == 1)
+        run_split<D>(ctx, wave, nblk, qreg, qpos, m_run, l_run, oacc, a.c);
+    else if (TR == 2)
+        run_shared<D, 2>(ctx, xbuf, wave, lane, nblk, qreg, qpos, m_run, l_run, oacc, a.c);
+    else
+        run_shared<D, 4>(ctx, xbuf, wave, lane, nblk, qreg, qpos, m_run, l_run, oacc, a.c);
+
+    // ---- merge the token parts in LDS and write one partial result per (chunk, row):
+    //      m = running maximum of the raw scores, l = sum of exp, acc = un-normalised weighted values
+    const float l_tot = wave_row_sum(l_run);
+    __syncthreads();  // the exchange buffer is dead from here on; the merge buffer takes its place
+    if (g == 0) {
+        mM[wave * 16 + n16] = m_run;
+        mL[wave * 16 + n16] = l_tot;
+    }
+    if (D == 128 || g < 2) {
+        // this lane owns d in [32g, 32g+32) of row n16: d = 32g + 8i + c'
+        float *dst = mO + (wave * 16 + n16) * OP + 32 * g;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f32x4 lo4 = {oacc[0][i], oacc[1][i], oacc[2][i], oacc[3][i]};
+            const f32x4 hi4 = {oacc[4][i], oacc[5][i], oacc[6][i], oacc[7][i]};
+            *reinterpret_cast<f32x4 *>(dst + 8 * i) = lo4;
+            *reinterpret_cast<f32x4 *>(dst + 8 * i + 4) = hi4;
+        }
+    }
+    __syncthreads();
+
+    constexpr int EPL = D / 16;  // floats of a row per lane when 16 lanes share a row
+    const int NP = kWaves / TR;  // parts to merge per row
+    const int rr = lane >> 4, dc = lane & 15;
+    for (int ps = 0; ps < TR; ++ps) {
+        const int gr = 4 * TR * wave + 4 * ps + rr;  // row of the task: 16 * tile + n
+        const int tile = gr >> 4, n = gr & 15;
+        const int r = 16 * (tile0 + tile) + n;
+        if (tile >= ntiles || r >= R) continue;
+        float M = -INFINITY;
+        for (int s = 0; s < NP; ++s) M = fmaxf(M, mM[(tile + TR * s) * 16 + n]);
+        const float m_use = (M == -INFINITY) ? 0.f : M;
+        float L = 0.f;
+        float o[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[e] = 0.f;
+        for (int s = 0; s < NP; ++s) {
+            const int src = tile + TR * s;
+            const float w = __builtin_amdgcn_exp2f((mM[src * 16 + n] - m_use) * a.c);
+            L += w * mL[src * 16 + n];
+            const float *row = mO + (src * 16 + n) * OP + EPL * dc;
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4) {
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(row + e);
+                o[e] += w * x[0];
+                o[e + 1] += w * x[1];
+                o[e + 2] += w * x[2];
+                o[e + 3] += w * x[3];
+            }
+        }
+        const int pl = r / a.G, gh = r - pl * a.G;
+        const size_t ro = (size_t)(slot_base + pl) * a.Hq + (size_t)h * a.G + gh;
+        if (dc == 0) {
+            a.part_m[ro] = M;
+            a.part_l[ro] = L;
+        }
+        float *dst = a.part_acc + ro * D + EPL * dc;
+#pragma unroll
+        for (int e = 0; e < EPL; e += 4) *reinterpret_cast<f32x4 *>(dst + e) = f32x4{o[e], o[e + 1], o[e + 2], o[e + 3]};
+    }
+}
+
+// Stage 2: tree-topology-aware global reduction (eq. 1 with the largest maximum subtracted).
+// One wave per (query, query head).  Weights are computed with lanes across the query's slots;
+// the weighted rows are then summed with D/4 lanes per row (128-bit loads), several rows at a time.
 template <int D>
 __global__ __launch_bounds__(64) void deft_stage2(Stage2Args a) {
-    constexpr int E = D / 64;  // output elements per lane
+    constexpr int LPR = D / 4;     // lanes per partial row
+    constexpr int RPI = 64 / LPR;  // rows per iteration
     const int lane = threadIdx.x;
     const int p = blockIdx.x / a.Hq;
     const int qh = blockIdx.x - p * a.Hq;
-    const int s0 = a.q_part_ptr[p], s1 = a.q_part_ptr[p + 1];
+    const int s0 = a.q_part_ptr[p];
+    const int n = a.q_part_ptr[p + 1] - s0;
+    const int sub = lane / LPR, col = lane - sub * LPR;
 
     float mx = -INFINITY;
-    for (int i = s0 + lane; i < s1; i += 64) mx = fmaxf(mx, a.part_m[(size_t)a.q_part_slot[i] * a.Hq + qh]);
+    for (int i = lane; i < n; i += 64) mx = fmaxf(mx, a.part_m[(size_t)a.q_part_slot[s0 + i] * a.Hq + qh]);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
 
-    float acc[E];
-#pragma unroll
-    for (int e = 0; e < E; ++e) acc[e] = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float lsum = 0.f;
     if (mx != -INFINITY) {
-        for (int i = s0; i < s1; ++i) {
-            const size_t ro = (size_t)a.q_part_slot[i] * a.Hq + qh;
-            const float w = __builtin_amdgcn_exp2f((a.part_m[ro] - mx) * a.c);
-            lsum += w * a.part_l[ro];
-            const float *src = a.part_acc + ro * D + E * lane;
+        for (int base = 0; base < n; base += 64) {
+            const int i = base + lane;
+            float w = 0.f;
+            int slot = 0;
+            if (i < n) {
+                slot = a.q_part_slot[s0 + i];
+                const size_t ro = (size_t)slot * a.Hq + qh;
+                w = __builtin_amdgcn_exp2f((a.part_m[ro] - mx) * a.c);
+                lsum += w * a.part_l[ro];
+            }
+            const int cnt = min(64, n - base);
+            for (int j = 0; j < cnt; j += 4 * RPI) {
+                // four independent row loads per trip; rows past cnt get weight 0 and read slot 0, which exists
+                float wj[4];
+                f32x4 x[4];
 #pragma unroll
-            for (int e = 0; e < E; ++e) acc[e] += w * src[e];
+                for (int u = 0; u < 4; ++u) {
+                    const int jj = j + u * RPI + sub;
+                    const float ws = __shfl(w, jj & 63);
+                    const int sj = __shfl(slot, jj & 63);
+                    wj[u] = jj < cnt ? ws : 0.f;
+                    const int sr = jj < cnt ? sj : 0;
+                    x[u] = *reinterpret_cast<const f32x4 *>(a.part_acc + ((size_t)sr * a.Hq + qh) * D + 4 * col);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc += wj[u] * x[u];
+            }
         }
     }
+#pragma unroll
+    for (int o = 32; o >= LPR; o >>= 1) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], o);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lsum += __shfl_xor(lsum, o);
+    if (sub != 0) return;
     const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
-    const size_t oo = ((size_t)a.q_order[p] * a.Hq + qh) * D + E * lane;
+    const size_t oo = ((size_t)a.q_order[p] * a.Hq + qh) * D + 4 * col;
     if (a.out_f32) {
-        float *o = reinterpret_cast<float *>(a.out) + oo;
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[e] = acc[e] * inv;
+        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.out) + oo) = acc * inv;
     } else {
-        __bf16 *o = reinterpret_cast<__bf16 *>(a.out) + oo;
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[e] = (__bf16)(acc[e] * inv);
+        typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+        u32x2 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv)};
+        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(a.out) + oo) = pk;
     }
 }
 
@@ -322,30 +549,28 @@ bool hip_ok(hipError_t e, const char *what) {
     return false;
 }
 
-template <int D, int NT>
-bool launch_stage1(const Stage1Args &args, hipStream_t stream) {
-    if (args.n_items == 0) return true;
-    const size_t lds = 3 * (size_t)args.chunk_size * sizeof(int32_t);
-    const unsigned grid = (unsigned)args.n_items * (unsigned)args.Hkv;
-    hipLaunchKernelGGL((deft_stage1<D, NT>), dim3(grid), dim3(64), lds, stream, args);
-    return hip_ok(hipGetLastError(), "deft_stage1 launch");
-}
-
 template <int D>
-bool launch_stage1_lists(const deft::Schedule &S, Stage1Args a1, const uint8_t *image, hipStream_t stream) {
-    for (const deft::ItemList &L : S.lists) {
-        a1.items = reinterpret_cast<const int32_t *>(image + L.offset);
-        a1.n_items = L.n_items;
-        bool ok = true;
-        switch (L.nt) {
-            case 1: ok = launch_stage1<D, 1>(a1, stream); break;
-            case 2: ok = launch_stage1<D, 2>(a1, stream); break;
-            case 4: ok = launch_stage1<D, 4>(a1, stream); break;
-            default: ok = false; g_hip_error = "unknown row-tile class"; break;
-        }
-        if (!ok) return false;
+bool launch_stage1(const deft::Schedule &S, Stage1Args a1, const uint8_t *image, hipStream_t stream) {
+    a1.items = reinterpret_cast<const int32_t *>(image + S.off_items);
+    a1.n_items = S.n_items;
+    if (a1.n_items == 0) return true;
+    const size_t lds = kXbufBytes + 3 * (size_t)a1.chunk_size * sizeof(int32_t);
+    // the kernel may use more than the default 64 KB of dynamic LDS: raise the limit once per device
+    static std::atomic<uint64_t> configured[2];  // bit i set: done on device i, per head dimension
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return false;
+    std::atomic<uint64_t> &mask = configured[D == 128];
+    if (dev < 0 || dev >= 64 || !((mask.load(std::memory_order_acquire) >> dev) & 1)) {
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void *>(&deft_stage1<D>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        kXbufBytes + 3 * DEFT_MAX_CHUNK * (int)sizeof(int32_t)),
+                    "deft_stage1 LDS size"))
+            return false;
+        if (dev >= 0 && dev < 64) mask.fetch_or(1ull << dev, std::memory_order_release);
     }
-    return true;
+    const unsigned grid = (unsigned)a1.n_items * (unsigned)a1.Hkv;
+    hipLaunchKernelGGL((deft_stage1<D>), dim3(grid), dim3(64 * kWaves), lds, stream, a1);
+    return hip_ok(hipGetLastError(), "deft_stage1 launch");
 }
 
 template <int D>
@@ -374,8 +599,7 @@ int prepare(const deft_plan_t *plan, const void *dev_image, int32_t Hq, int32_t 
     call.S = deft::find_schedule(plan, Hq / Hkv);
     if (!call.S) return DEFT_ENOTREADY;
     if (workspace_bytes < deft_workspace_bytes(plan, Hq, Hkv, d)) return DEFT_EWORKSPACE;
-    for (const deft::ItemList &L : call.S->lists)
-        if ((int64_t)L.n_items * Hkv > INT32_MAX) return DEFT_EINVAL;  // grid sizes are 32-bit
+    if ((int64_t)call.S->n_items * Hkv > INT32_MAX) return DEFT_EINVAL;  // grid sizes are 32-bit
     if ((int64_t)plan->nq * Hq > INT32_MAX) return DEFT_EINVAL;
     const size_t rows = (size_t)plan->n_slots() * (size_t)Hq;
     call.img = static_cast<const uint8_t *>(dev_image);
@@ -401,22 +625,19 @@ int run_stage1(const deft_plan_t *plan, const Call &call, const void *q, const v
     a1.part_acc = call.acc;
     a1.part_m = call.pm;
     a1.part_l = call.pl;
-    a1.chunk_seg_ptr = at(S.off_chunk_seg_ptr);
     a1.seg_tok_begin = at(S.off_seg_tok_begin);
     a1.seg_len = at(S.off_seg_len);
     a1.seg_qlo = at(S.off_seg_qlo);
     a1.seg_qhi = at(S.off_seg_qhi);
-    a1.chunk_qlo = at(S.off_chunk_qlo);
-    a1.chunk_qhi = at(S.off_chunk_qhi);
-    a1.chunk_slot_base = at(S.off_chunk_slot_base);
+    a1.seg_off = at(S.off_seg_off);
     a1.q_order = at(S.off_q_order);
     a1.Hq = Hq;
     a1.Hkv = Hkv;
     a1.G = Hq / Hkv;
     a1.chunk_size = plan->chunk_size;
     a1.c = call.c;
-    const bool ok = d == 128 ? launch_stage1_lists<128>(S, a1, call.img, call.stream)
-                             : launch_stage1_lists<64>(S, a1, call.img, call.stream);
+    const bool ok = d == 128 ? launch_stage1<128>(S, a1, call.img, call.stream)
+                             : launch_stage1<64>(S, a1, call.img, call.stream);
     return ok ? DEFT_OK : DEFT_EHIP;
 }
 

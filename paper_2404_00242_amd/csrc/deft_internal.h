@@ -10,13 +10,25 @@
 
 namespace deft {
 
-// One launch list of stage-1 work items.  An item is a (chunk, 16-row-tile range) pair;
-// the kernel instance NT handles up to NT row tiles per wave.  Each item is two int32:
-// {chunk, tile_begin | n_tiles << 24}.
-struct ItemList {
-    int nt = 0;               // row tiles per wave of the kernel instance that runs this list
-    int32_t n_items = 0;
-    size_t offset = 0;        // byte offset of the item array inside the device image
+// A stage-1 task is a (chunk, range of up to four 16-row tiles) pair; with the KV head taken from the
+// workgroup id it is the job of one workgroup.  Its descriptor is kItemInts int32, read with scalar
+// loads, and carries everything the workgroup needs to start streaming a single-segment chunk
+// without touching any other table.
+constexpr int kItemInts = 16;
+constexpr int kMaxTilesPerTask = 4;
+enum ItemField {
+    kItChunk = 0,     // chunk id
+    kItTile0 = 1,     // first 16-row tile of the chunk's group handled by this task
+    kItNTiles = 2,    // number of tiles, 1..kMaxTilesPerTask
+    kItSeg0 = 3,      // first segment of the chunk
+    kItNSeg = 4,      // number of segments
+    kItQlo = 5,       // chunk_qlo
+    kItWidth = 6,     // chunk_qhi - chunk_qlo
+    kItSlotBase = 7,  // chunk_slot_base
+    kItLen = 8,       // tokens in the chunk
+    kItBegin0 = 9,    // first segment: physical row of its first token,
+    kItSegQlo0 = 10,  //                its query interval
+    kItSegQhi0 = 11,
 };
 
 // Launch schedule + image layout for one Hq/Hkv ratio.
@@ -24,10 +36,11 @@ struct Schedule {
     int32_t group = 0;        // G = Hq / Hkv, rows per query within one KV head
     size_t bytes = 0;         // total image size
     // byte offsets of the canonical arrays inside the image
-    size_t off_chunk_seg_ptr = 0, off_seg_tok_begin = 0, off_seg_len = 0, off_seg_qlo = 0, off_seg_qhi = 0;
-    size_t off_chunk_qlo = 0, off_chunk_qhi = 0, off_chunk_slot_base = 0, off_q_order = 0;
+    size_t off_seg_tok_begin = 0, off_seg_len = 0, off_seg_qlo = 0, off_seg_qhi = 0, off_seg_off = 0;
+    size_t off_q_order = 0;
     size_t off_q_part_ptr = 0, off_q_part_slot = 0;
-    std::vector<ItemList> lists;
+    size_t off_items = 0;     // task descriptors
+    int32_t n_items = 0;
     std::vector<uint8_t> host_image;  // packed image, kept for repeated uploads
 };
 

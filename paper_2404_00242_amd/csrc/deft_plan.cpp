@@ -259,11 +259,11 @@ extern "C" const char *deft_strerror(int status) {
 // ------------------------------------------------------------------------------------------------
 // Launch schedule.  The rows of a chunk's group, seen from one KV head, are (query of the group) x
 // (the G query heads that read this KV head): R = w * G rows, tiled 16 at a time (the N dimension
-// of the 16x16x32 MFMA).  A wave carries up to NT row tiles through the whole chunk, so narrow
-// groups run with few registers per wave and wide groups are cut into several waves that re-read
-// the chunk from L2.  The kernel numbers its workgroups item * Hkv + kv_head, so the items that
-// re-read one chunk for one head sit Hkv workgroups apart; with Hkv a multiple of 8 and workgroups
-// dealt round-robin to the 8 XCDs they meet in the same L2.
+// of the 16x16x32 MFMA).  A task covers up to four row tiles of one chunk and is run by a workgroup
+// of four waves; wider groups are cut into several tasks that re-read the chunk from L2.  The kernel
+// numbers its workgroups task * Hkv + kv_head, so the tasks that re-read one chunk for one head sit
+// Hkv workgroups apart; with Hkv a multiple of 8 and workgroups dealt round-robin to the 8 XCDs they
+// meet in the same L2.
 // ------------------------------------------------------------------------------------------------
 namespace deft {
 
@@ -272,18 +272,33 @@ static size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
     S.group = G;
     const int32_t m = P->n_chunks();
-    static const int kClasses[3] = {1, 2, 4};
-    std::vector<std::vector<int32_t>> items(3);
+    std::vector<int32_t> items;
+    std::vector<int32_t> seg_off(P->n_segs(), 0);
     for (int32_t c = 0; c < m; ++c) {
-        const int64_t rows = (int64_t)(P->chunk_qhi[c] - P->chunk_qlo[c]) * G;
+        const int32_t s0 = P->chunk_seg_ptr[c], s1 = P->chunk_seg_ptr[c + 1];
+        int32_t len = 0;
+        for (int32_t s = s0; s < s1; ++s) {
+            seg_off[s] = len;
+            len += P->seg_len[s];
+        }
+        const int32_t width = P->chunk_qhi[c] - P->chunk_qlo[c];
+        const int64_t rows = (int64_t)width * G;
         const int32_t tiles = (int32_t)((rows + 15) / 16);
-        if (tiles <= 0) continue;
-        int cls = tiles == 1 ? 0 : (tiles == 2 ? 1 : 2);
-        const int nt = kClasses[cls];
-        for (int32_t t0 = 0; t0 < tiles; t0 += nt) {
-            int32_t cnt = std::min(nt, tiles - t0);
-            items[cls].push_back(c);
-            items[cls].push_back(t0 | (cnt << 24));
+        for (int32_t t0 = 0; t0 < tiles; t0 += kMaxTilesPerTask) {
+            int32_t d[kItemInts] = {0};
+            d[kItChunk] = c;
+            d[kItTile0] = t0;
+            d[kItNTiles] = std::min<int32_t>(kMaxTilesPerTask, tiles - t0);
+            d[kItSeg0] = s0;
+            d[kItNSeg] = s1 - s0;
+            d[kItQlo] = P->chunk_qlo[c];
+            d[kItWidth] = width;
+            d[kItSlotBase] = P->chunk_slot_base[c];
+            d[kItLen] = len;
+            d[kItBegin0] = P->seg_tok_begin[s0];
+            d[kItSegQlo0] = P->seg_qlo[s0];
+            d[kItSegQhi0] = P->seg_qhi[s0];
+            items.insert(items.end(), d, d + kItemInts);
         }
     }
 
@@ -294,42 +309,31 @@ static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
         return at;
     };
     const int32_t nseg = P->n_segs(), nq = P->nq, slots = P->n_slots();
-    S.off_chunk_seg_ptr = place(m + 1);
     S.off_seg_tok_begin = place(nseg);
     S.off_seg_len = place(nseg);
     S.off_seg_qlo = place(nseg);
     S.off_seg_qhi = place(nseg);
-    S.off_chunk_qlo = place(m);
-    S.off_chunk_qhi = place(m);
-    S.off_chunk_slot_base = place(m + 1);
+    S.off_seg_off = place(nseg);
     S.off_q_order = place(nq);
     S.off_q_part_ptr = place(nq + 1);
     S.off_q_part_slot = place(slots);
-    S.lists.clear();
-    for (int k = 0; k < 3; ++k) {
-        ItemList L;
-        L.nt = kClasses[k];
-        L.n_items = (int32_t)(items[k].size() / 2);
-        L.offset = place(items[k].size());
-        S.lists.push_back(L);
-    }
+    off = (off + 63) & ~(size_t)63;  // descriptors are aligned 64-byte records
+    S.n_items = (int32_t)(items.size() / kItemInts);
+    S.off_items = place(items.size());
     S.bytes = std::max<size_t>(off, 16);
     S.host_image.assign(S.bytes, 0);
     auto put = [&](size_t at, const std::vector<int32_t> &v) {
         if (!v.empty()) std::memcpy(S.host_image.data() + at, v.data(), v.size() * sizeof(int32_t));
     };
-    put(S.off_chunk_seg_ptr, P->chunk_seg_ptr);
     put(S.off_seg_tok_begin, P->seg_tok_begin);
     put(S.off_seg_len, P->seg_len);
     put(S.off_seg_qlo, P->seg_qlo);
     put(S.off_seg_qhi, P->seg_qhi);
-    put(S.off_chunk_qlo, P->chunk_qlo);
-    put(S.off_chunk_qhi, P->chunk_qhi);
-    put(S.off_chunk_slot_base, P->chunk_slot_base);
+    put(S.off_seg_off, seg_off);
     put(S.off_q_order, P->q_order);
     put(S.off_q_part_ptr, P->q_part_ptr);
     put(S.off_q_part_slot, P->q_part_slot);
-    for (int k = 0; k < 3; ++k) put(S.lists[k].offset, items[k]);
+    put(S.off_items, items);
 }
 
 const Schedule *get_schedule(const deft_plan_t *plan, int32_t group) {
