@@ -148,24 +148,26 @@ def main():
         plans.append(prepare())
     plan_us = (time.perf_counter() - tp0) * 1e5
 
-    # second pass: per-stage durations with events on the launch stream
+    # second pass: per-stage durations with events on the launch stream.  Each stage's launches for all
+    # layers run back to back between two events, so the mean includes the gap between two dispatches
+    # but not the other stage.
     h = plans[-1]
     n_prof = max(args.steps, 1)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_prof * L)]
-    torch.cuda.synchronize()
-    i = 0
+    s1_ms, s2_ms = [], []
     for _ in range(n_prof):
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        e0.record(stream)
         for (qp, kp, vpp, op) in layer_ptrs:
-            e0, e1, e2 = ev[i]
-            i += 1
-            e0.record(stream)
             lib.deft_stage1_partial_attention(h, imgp, qp, kp, vpp, Hq, Hkv, d, 0.0, wsp, ws_bytes, st)
-            e1.record(stream)
+        e1.record(stream)
+        for (qp, kp, vpp, op) in layer_ptrs:
             lib.deft_stage2_global_reduction(h, imgp, op, Hq, Hkv, d, 0.0, 0, wsp, ws_bytes, st)
-            e2.record(stream)
-    torch.cuda.synchronize()
-    s1_us = float(np.mean([e[0].elapsed_time(e[1]) for e in ev])) * 1e3
-    s2_us = float(np.mean([e[1].elapsed_time(e[2]) for e in ev])) * 1e3
+        e2.record(stream)
+        torch.cuda.synchronize()
+        s1_ms.append(e0.elapsed_time(e1) / L)
+        s2_ms.append(e1.elapsed_time(e2) / L)
+    s1_us = float(np.mean(s1_ms)) * 1e3
+    s2_us = float(np.mean(s2_ms)) * 1e3
 
     kv_bytes = view["n_flat"] * Hkv * 2 * d * 2  # K and V of every reached token, once per KV head
     achieved = kv_bytes / (s1_us * 1e-6) / 1e9

@@ -14,7 +14,8 @@ import os
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libdeft.so")
+# DEFT_LIB lets a developer point the binding at another build of the same library (A/B timing runs)
+LIB_PATH = os.environ.get("DEFT_LIB") or os.path.join(_PKG, "libdeft.so")
 
 DEFT_OUT_BF16 = 0
 DEFT_OUT_F32 = 1

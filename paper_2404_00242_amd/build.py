@@ -19,7 +19,7 @@ def hipcc_command(out: str = LIB, extra=()):
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wno-unused-function",
         "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-        *extra,
+        *extra, *os.environ.get("DEFT_EXTRA_FLAGS", "").split(),
         *[os.path.join(CSRC, s) for s in SOURCES],
         "-o", out,
     ]

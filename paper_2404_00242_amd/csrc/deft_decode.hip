@@ -26,6 +26,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 
@@ -46,6 +47,9 @@ struct Stage1Args {
     const int32_t *items;  // deft::kItemInts int32 per work item, see deft_internal.h
     int32_t n_items, Hq, Hkv, G, chunk_size;
     float c;  // scale * log2(e): probabilities are 2^((s - m) * c)
+#ifdef DEFT_TRACE
+    unsigned long long *trace;  // developer build only: 4 timestamps per wave
+#endif
 };
 
 struct Stage2Args {
@@ -78,6 +82,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 
 constexpr int kWaves = 4;              // waves per stage-1 workgroup
 constexpr int kXbufBytes = 64 * 1024;  // LDS register-exchange area: 2 token parts x 2 stages x 16 KB
+static_assert(4 * DEFT_MAX_CHUNK * sizeof(int32_t) <= kXbufBytes, "piece records are parked in the exchange area");
 
 // What a wave needs to know about its chunk to address tokens.
 struct ChunkCtx {
@@ -117,11 +122,24 @@ __device__ __forceinline__ void load_block(KVRegs<D> &r, const ChunkCtx &c, int 
     }
 }
 
+// Running softmax state of one row (held redundantly by the row's four lanes).
+//   m  : reference maximum of the raw scores, -inf while the row has seen no visible token
+//   mc : (m, or 0 while m is -inf) * cs, the value subtracted inside the exponential
+//   l  : this lane's share of sum exp2(s * cs - mc)
+// The reference is only raised when some score exceeds it by more than kLazyLog2 / cs (probabilities may
+// then reach 2^kLazyLog2, harmless in bf16 and fp32); otherwise a block costs no cross-lane traffic and
+// no rescaling of the accumulators.  Any reference gives the same (m, l, acc) up to rounding, because the
+// merge of eq. 1 only needs the three to be consistent.
+struct RowState {
+    float m, mc, l;
+};
+constexpr float kLazyLog2 = 8.0f;
+
 // Online-softmax step of one wave over one 32-token block, for its 16-row tile.
 template <int D>
 __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx &c, int x0,
-                                              const bf16x8 (&qreg)[D / 32], const int qpos, float &m_run,
-                                              float &l_run, f32x4 (&oacc)[8], const float cs) {
+                                              const bf16x8 (&qreg)[D / 32], const int qpos, RowState &st,
+                                              f32x4 (&oacc)[8], const float cs, const float lazy) {
     constexpr int KK = D / 32;
     // S^T = K Q^T : sacc[a][i] is the score of token 16a + 4g + i against row n16
     f32x4 sacc[2];
@@ -134,53 +152,60 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
         sacc[aa] = acc;
     }
 
-    // mask: a token is visible to plan position qpos iff qlo <= qpos < qhi of the node piece it belongs to
-    float mx = -INFINITY;
+    // mask: a token is visible to plan position qpos iff qlo <= qpos < qhi of the node piece it belongs to.
+    // A full block of a single-piece chunk is visible to every row of the chunk's group: nothing to mask
+    // (rows past the group's end have Q = 0, finite scores, and are never written).
+    if (!(c.uniform && x0 + 32 <= c.clen)) {
 #pragma unroll
-    for (int aa = 0; aa < 2; ++aa) {
-        const int xv = x0 + 16 * aa + 4 * c.g;
-        i32x4 qlo, qhi;
-        if (c.uniform) {
+        for (int aa = 0; aa < 2; ++aa) {
+            const int xv = x0 + 16 * aa + 4 * c.g;
+            i32x4 qlo, qhi;
+            if (c.uniform) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool in = xv + i < c.clen;
+                    qlo[i] = in ? c.qlo0 : 0;
+                    qhi[i] = in ? c.qhi0 : 0;
+                }
+            } else {
+                qlo = *reinterpret_cast<const i32x4 *>(&c.s_qlo[xv]);
+                qhi = *reinterpret_cast<const i32x4 *>(&c.s_qhi[xv]);
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const bool in = xv + i < c.clen;
-                qlo[i] = in ? c.qlo0 : 0;
-                qhi[i] = in ? c.qhi0 : 0;
+                const bool on = (qpos >= qlo[i]) && (qpos < qhi[i]);
+                sacc[aa][i] = on ? sacc[aa][i] : -INFINITY;
             }
-        } else {
-            qlo = *reinterpret_cast<const i32x4 *>(&c.s_qlo[xv]);
-            qhi = *reinterpret_cast<const i32x4 *>(&c.s_qhi[xv]);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const bool on = (qpos >= qlo[i]) && (qpos < qhi[i]);
-            const float sv = on ? sacc[aa][i] : -INFINITY;
-            sacc[aa][i] = sv;
-            mx = fmaxf(mx, sv);
         }
     }
-    mx = wave_row_max(mx);
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * cs);
-    m_run = m_new;
-    const float mc = m_use * cs;
+    float mx = fmaxf(fmaxf(fmaxf(sacc[0][0], sacc[0][1]), fmaxf(sacc[0][2], sacc[0][3])),
+                     fmaxf(fmaxf(sacc[1][0], sacc[1][1]), fmaxf(sacc[1][2], sacc[1][3])));
+    if (__any(mx > st.m + lazy)) {
+        // raise the reference of every row to its exact running maximum and rescale what was accumulated
+        mx = wave_row_max(mx);
+        const float m_new = fmaxf(st.m, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(st.m * cs - m_use * cs);  // exp2(-inf) = 0 on the first raise
+        st.m = m_new;
+        st.mc = m_use * cs;
+        st.l *= alpha;
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) oacc[cc] *= alpha;
+    }
     float pv[8];
     float psum = 0.f;
 #pragma unroll
     for (int aa = 0; aa < 2; ++aa)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const float e = __builtin_amdgcn_exp2f(fmaf(sacc[aa][i], cs, -mc));
+            const float e = __builtin_amdgcn_exp2f(fmaf(sacc[aa][i], cs, -st.mc));
             pv[4 * aa + i] = e;
             psum += e;
         }
-    l_run = l_run * alpha + psum;
+    st.l += psum;
     const u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]),
                       pack_bf16(pv[6], pv[7])};
     const bf16x8 preg = __builtin_bit_cast(bf16x8, pk);
-#pragma unroll
-    for (int cc = 0; cc < 8; ++cc) oacc[cc] *= alpha;
 
     // O^T += V^T P^T.  The V^T operand of product c' = 2*c2 + {0,1} is a 16-bit interleave of token pairs:
     // vt[p] = {V[tok 2p][8*n16 + c'], V[tok 2p+1][8*n16 + c']}
@@ -201,26 +226,29 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
 }
 
 // ---- token-split path (groups of one row tile): every wave streams its own blocks, two in flight ----
+// wave w takes blocks w, w+4, w+8, ... (neighbouring waves read neighbouring rows at the same time)
 template <int D>
-__device__ __forceinline__ void run_split(const ChunkCtx &ctx, int wave, int nblk, const bf16x8 (&qreg)[D / 32],
-                                          int qpos, float &m_run, float &l_run, f32x4 (&oacc)[8], float cs) {
-    // wave w takes blocks w, w+4, w+8, ... (neighbouring waves read neighbouring rows at the same time)
+struct SplitPipe {
     KVRegs<D> b0, b1;
-    int blk = wave;
-    if (blk < nblk) load_block<D>(b0, ctx, blk * 32);
-    if (blk + kWaves < nblk) load_block<D>(b1, ctx, (blk + kWaves) * 32);
-    for (; blk < nblk; blk += 2 * kWaves) {
-        compute_block<D>(b0, ctx, blk * 32, qreg, qpos, m_run, l_run, oacc, cs);
-        if (blk + 2 * kWaves < nblk) load_block<D>(b0, ctx, (blk + 2 * kWaves) * 32);
-        if (blk + kWaves < nblk) {
-            compute_block<D>(b1, ctx, (blk + kWaves) * 32, qreg, qpos, m_run, l_run, oacc, cs);
-            if (blk + 3 * kWaves < nblk) load_block<D>(b1, ctx, (blk + 3 * kWaves) * 32);
+    __device__ __forceinline__ void prime(const ChunkCtx &ctx, int wave, int nblk) {
+        if (wave < nblk) load_block<D>(b0, ctx, wave * 32);
+        if (wave + kWaves < nblk) load_block<D>(b1, ctx, (wave + kWaves) * 32);
+    }
+    __device__ __forceinline__ void run(const ChunkCtx &ctx, int wave, int nblk, const bf16x8 (&qreg)[D / 32], int qpos,
+                                        RowState &rs, f32x4 (&oacc)[8], float cs, float lazy) {
+        for (int blk = wave; blk < nblk; blk += 2 * kWaves) {
+            compute_block<D>(b0, ctx, blk * 32, qreg, qpos, rs, oacc, cs, lazy);
+            if (blk + 2 * kWaves < nblk) load_block<D>(b0, ctx, (blk + 2 * kWaves) * 32);
+            if (blk + kWaves < nblk) {
+                compute_block<D>(b1, ctx, (blk + kWaves) * 32, qreg, qpos, rs, oacc, cs, lazy);
+                if (blk + 3 * kWaves < nblk) load_block<D>(b1, ctx, (blk + 3 * kWaves) * 32);
+            }
         }
     }
-}
+};
 
 // ---- row-split path (groups of TR = 2 or 4 row tiles): the TR waves that work on the same blocks each
-//      fetch 1/TR of a block from HBM and pass it to the others through LDS, so the block is read once ----
+//      fetch 1/TR of a block from HBM and pass it to the others through LDS, so the block is read once.
 template <int D, int TR>
 struct Share {
     static constexpr int KK = D / 32;
@@ -246,7 +274,7 @@ __device__ __forceinline__ void share_issue(Share<D, TR> &s, const ChunkCtx &c, 
 template <int D, int TR>
 __device__ __forceinline__ void share_step(Share<D, TR> &s, const ChunkCtx &c, u32x4 *xs, int t, int lane, int blk,
                                            int next_blk, int nblk, const bf16x8 (&qreg)[D / 32], int qpos,
-                                           float &m_run, float &l_run, f32x4 (&oacc)[8], float cs) {
+                                           RowState &rs, f32x4 (&oacc)[8], float cs, float lazy) {
     using S = Share<D, TR>;
     constexpr int KK = D / 32;
     const int am = t / S::H, hk = t % S::H;
@@ -267,30 +295,47 @@ __device__ __forceinline__ void share_step(Share<D, TR> &s, const ChunkCtx &c, u
             for (int kk = 0; kk < KK; ++kk) r.k[aa][kk] = __builtin_bit_cast(bf16x8, xs[(aa * KK + kk) * 64 + lane]);
 #pragma unroll
         for (int j = 0; j < 8; ++j) r.v[j] = xs[(2 * KK + j) * 64 + lane];
-        compute_block<D>(r, c, blk * 32, qreg, qpos, m_run, l_run, oacc, cs);
+        compute_block<D>(r, c, blk * 32, qreg, qpos, rs, oacc, cs, lazy);
     }
 }
 
 template <int D, int TR>
-__device__ __forceinline__ void run_shared(const ChunkCtx &ctx, u32x4 *xbuf, int wave, int lane, int nblk,
-                                           const bf16x8 (&qreg)[D / 32], int qpos, float &m_run, float &l_run,
-                                           f32x4 (&oacc)[8], float cs) {
+struct SharedPipe {
     using S = Share<D, TR>;
-    constexpr int NP = kWaves / TR;  // token parts: part p takes blocks p, p+NP, ...
-    const int t = wave % TR, part = wave / TR;
-    const int iters = (nblk + NP - 1) / NP;  // the same for every wave: barriers stay aligned
-    u32x4 *xb = xbuf + (size_t)part * 2 * S::NSLOT * 64;
-    Share<D, TR> sa, sb;
-    int blk = part;
-    if (blk < nblk) share_issue<D, TR>(sa, ctx, t, blk * 32);
-    if (blk + NP < nblk) share_issue<D, TR>(sb, ctx, t, (blk + NP) * 32);
-    for (int it = 0; it < iters; it += 2, blk += 2 * NP) {
-        share_step<D, TR>(sa, ctx, xb, t, lane, blk, blk + 2 * NP, nblk, qreg, qpos, m_run, l_run, oacc, cs);
-        if (it + 1 < iters)
-            share_step<D, TR>(sb, ctx, xb + S::NSLOT * 64, t, lane, blk + NP, blk + 3 * NP, nblk, qreg, qpos, m_run,
-                              l_run, oacc, cs);
+    static constexpr int NP = kWaves / TR;  // token parts: part p takes blocks p, p+NP, ...
+#ifndef DEFT_DEPTH_NUM
+#define DEFT_DEPTH_NUM 2
+#endif
+    static constexpr int DEPTH = DEFT_DEPTH_NUM * TR / 2;  // blocks whose shares a wave keeps in flight (3/4 of the
+                                              // token-split path's bytes; the operands read back from LDS need the rest)
+    Share<D, TR> st[DEPTH];
+    __device__ __forceinline__ void prime(const ChunkCtx &ctx, int wave, int nblk) {
+        const int t = wave % TR, part = wave / TR;
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u)
+            if (part + u * NP < nblk) share_issue<D, TR>(st[u], ctx, t, (part + u * NP) * 32);
     }
-}
+    __device__ __forceinline__ void run(const ChunkCtx &ctx, u32x4 *xbuf, int wave, int lane, int nblk,
+                                        const bf16x8 (&qreg)[D / 32], int qpos, RowState &rs, f32x4 (&oacc)[8],
+                                        float cs, float lazy) {
+        const int t = wave % TR, part = wave / TR;
+        const int iters = (nblk + NP - 1) / NP;  // the same for every wave: barriers stay aligned
+        u32x4 *xb = xbuf + (size_t)part * 2 * S::NSLOT * 64;
+        for (int it0 = 0; it0 < iters; it0 += DEPTH) {
+#pragma unroll
+            for (int u = 0; u < DEPTH; ++u) {
+                const int it = it0 + u;
+                if (it < iters) {
+                    const int blk = part + it * NP;
+                    // LDS exchange stages alternate; stage (it & 1) was last read two steps ago, before the
+                    // barrier of the previous step
+                    share_step<D, TR>(st[u], ctx, xb + (it & 1) * S::NSLOT * 64, t, lane, blk, blk + DEPTH * NP, nblk,
+                                      qreg, qpos, rs, oacc, cs, lazy);
+                }
+            }
+        }
+    }
+};
 
 // Stage 1: one workgroup of four waves per task = (chunk, KV head, up to 64 rows of the chunk's group).
 // The rows are (query of the group) x (query head reading this KV head), tiled 16 at a time.  A task with
@@ -314,12 +359,20 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     int32_t *s_qlo = s_row + a.chunk_size;
     int32_t *s_qhi = s_qlo + a.chunk_size;
 
+#ifdef DEFT_TRACE
+    const unsigned long long t_begin = wall_clock64();
+#endif
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15;
     const int g = lane >> 4;
+#ifdef DEFT_HEAD_MAJOR
+    const int h = blockIdx.x / a.n_items;
+    const int item = blockIdx.x - h * a.n_items;
+#else
     const int item = blockIdx.x / a.Hkv;
     const int h = blockIdx.x - item * a.Hkv;
+#endif
     const int32_t *it = a.items + (size_t)item * deft::kItemInts;
     const int tile0 = it[deft::kItTile0], ntiles = it[deft::kItNTiles];
     const int seg0 = it[deft::kItSeg0], nseg = it[deft::kItNSeg];
@@ -348,40 +401,45 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     // ---- chunks made of several node pieces: per-token table (physical row, interval of plan
     //      positions that attend) expanded from the plan's segment table into LDS
     if (nseg > 1) {
-        if (nseg <= 16) {
-            for (int s = seg0; s < seg0 + nseg; ++s) {
-                const int b = a.seg_tok_begin[s], n = a.seg_len[s], lo = a.seg_qlo[s], hi = a.seg_qhi[s];
-                const int off = a.seg_off[s];
-                for (int i = tid; i < n; i += 64 * kWaves) {
-                    s_row[off + i] = b + i;
-                    s_qlo[off + i] = lo;
-                    s_qhi[off + i] = hi;
-                }
-            }
-        } else {
-            for (int s = seg0 + tid; s < seg0 + nseg; s += 64 * kWaves) {
-                const int b = a.seg_tok_begin[s], n = a.seg_len[s], lo = a.seg_qlo[s], hi = a.seg_qhi[s];
-                const int off = a.seg_off[s];
-                for (int i = 0; i < n; ++i) {
-                    s_row[off + i] = b + i;
-                    s_qlo[off + i] = lo;
-                    s_qhi[off + i] = hi;
-                }
-            }
+        // the piece records are fetched with one thread per piece (one round trip for the whole chunk) and
+        // parked in the exchange area, which is idle until the main loop; then one thread per token finds its
+        // piece by bisection over the pieces' offsets
+        int32_t *p_off = reinterpret_cast<int32_t *>(s_raw);
+        int32_t *p_beg = p_off + DEFT_MAX_CHUNK;
+        int32_t *p_lo = p_beg + DEFT_MAX_CHUNK;
+        int32_t *p_hi = p_lo + DEFT_MAX_CHUNK;
+        for (int s = tid; s < nseg; s += 64 * kWaves) {
+            p_off[s] = a.seg_off[seg0 + s];
+            p_beg[s] = a.seg_tok_begin[seg0 + s];
+            p_lo[s] = a.seg_qlo[seg0 + s];
+            p_hi[s] = a.seg_qhi[seg0 + s];
         }
-        for (int i = clen + tid; i < nblk * 32; i += 64 * kWaves) {  // last block's padding: a real row, masked
-            s_row[i] = ctx.begin0;
-            s_qlo[i] = 0;
-            s_qhi[i] = 0;
+        __syncthreads();
+        for (int x = tid; x < nblk * 32; x += 64 * kWaves) {
+            if (x < clen) {
+                int lo = 0, hi = nseg - 1;  // largest s with p_off[s] <= x
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (p_off[mid] <= x) lo = mid; else hi = mid - 1;
+                }
+                s_row[x] = p_beg[lo] + (x - p_off[lo]);
+                s_qlo[x] = p_lo[lo];
+                s_qhi[x] = p_hi[lo];
+            } else {  // last block's padding: a real row, masked
+                s_row[x] = ctx.begin0;
+                s_qlo[x] = 0;
+                s_qhi[x] = 0;
+            }
         }
         __syncthreads();
     }
 
-    // ---- this wave's 16 rows, and Q as the B operand (resident for the whole chunk)
+    // ---- this wave's 16 rows; Q is the B operand, resident for the whole chunk.  It is fetched after the
+    //      first K/V loads have been issued so that its two dependent reads do not delay them.
     const int my_tile = wave % TR;
     int qpos = -1;
     bf16x8 qreg[KK];
-    {
+    auto load_q = [&]() {
         const int r = 16 * (tile0 + my_tile) + n16;
         const bool ok = (my_tile < ntiles) && (r < R);
         const int pl = r / a.G, gh = r - pl * a.G;
@@ -395,26 +453,58 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) qreg[kk] = __builtin_bit_cast(bf16x8, load16(qp + 32 * kk));
         }
-    }
+    };
 
-    float m_run = -INFINITY, l_run = 0.f;
+    RowState rs = {-INFINITY, 0.f, 0.f};
+    const float lazy = kLazyLog2 / a.c;
     f32x4 oacc[8];
 #pragma unroll
     for (int cc = 0; cc < 8; ++cc) oacc[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if (TR == 1)
-        run_split<D>(ctx, wave, nblk, qreg, qpos, m_run, l_run, oacc, a.c);
-    else if (TR == 2)
-        run_shared<D, 2>(ctx, xbuf, wave, lane, nblk, qreg, qpos, m_run, l_run, oacc, a.c);
-    else
-        run_shared<D, 4>(ctx, xbuf, wave, lane, nblk, qreg, qpos, m_run, l_run, oacc, a.c);
+#ifdef DEFT_TRACE
+    const unsigned long long t_pro = wall_clock64();
+#endif
+    if (TR == 1) {
+        SplitPipe<D> pipe;
+#ifndef DEFT_Q_LAST
+        load_q();
+        pipe.prime(ctx, wave, nblk);
+#else
+        pipe.prime(ctx, wave, nblk);
+        load_q();
+#endif
+        pipe.run(ctx, wave, nblk, qreg, qpos, rs, oacc, a.c, lazy);
+    } else if (TR == 2) {
+        SharedPipe<D, 2> pipe;
+#ifndef DEFT_Q_LAST
+        load_q();
+        pipe.prime(ctx, wave, nblk);
+#else
+        pipe.prime(ctx, wave, nblk);
+        load_q();
+#endif
+        pipe.run(ctx, xbuf, wave, lane, nblk, qreg, qpos, rs, oacc, a.c, lazy);
+    } else {
+        SharedPipe<D, 4> pipe;
+#ifndef DEFT_Q_LAST
+        load_q();
+        pipe.prime(ctx, wave, nblk);
+#else
+        pipe.prime(ctx, wave, nblk);
+        load_q();
+#endif
+        pipe.run(ctx, xbuf, wave, lane, nblk, qreg, qpos, rs, oacc, a.c, lazy);
+    }
 
+#ifdef DEFT_TRACE
+    const unsigned long long t_loop = wall_clock64();
+#endif
     // ---- merge the token parts in LDS and write one partial result per (chunk, row):
     //      m = running maximum of the raw scores, l = sum of exp, acc = un-normalised weighted values
-    const float l_tot = wave_row_sum(l_run);
+    const float l_tot = wave_row_sum(rs.l);
     __syncthreads();  // the exchange buffer is dead from here on; the merge buffer takes its place
     if (g == 0) {
-        mM[wave * 16 + n16] = m_run;
+        mM[wave * 16 + n16] = rs.m;
         mL[wave * 16 + n16] = l_tot;
     }
     if (D == 128 || g < 2) {
@@ -469,6 +559,15 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
 #pragma unroll
         for (int e = 0; e < EPL; e += 4) *reinterpret_cast<f32x4 *>(dst + e) = f32x4{o[e], o[e + 1], o[e + 2], o[e + 3]};
     }
+#ifdef DEFT_TRACE
+    if (a.trace && lane == 0) {
+        unsigned long long *t = a.trace + ((size_t)blockIdx.x * kWaves + wave) * 4;
+        t[0] = t_begin;
+        t[1] = t_pro;
+        t[2] = t_loop;
+        t[3] = wall_clock64();
+    }
+#endif
 }
 
 // Stage 2: tree-topology-aware global reduction (eq. 1 with the largest maximum subtracted).
@@ -636,6 +735,12 @@ int run_stage1(const deft_plan_t *plan, const Call &call, const void *q, const v
     a1.G = Hq / Hkv;
     a1.chunk_size = plan->chunk_size;
     a1.c = call.c;
+#ifdef DEFT_TRACE
+    {
+        const char *e = getenv("DEFT_TRACE_BUF");
+        a1.trace = e ? reinterpret_cast<unsigned long long *>(strtoull(e, nullptr, 0)) : nullptr;
+    }
+#endif
     const bool ok = d == 128 ? launch_stage1<128>(S, a1, call.img, call.stream)
                              : launch_stage1<64>(S, a1, call.img, call.stream);
     return ok ? DEFT_OK : DEFT_EHIP;
