@@ -109,16 +109,24 @@ __device__ __forceinline__ int tok_row(const ChunkCtx &c, int x) {
     return c.uniform ? c.begin0 + min(x, c.clen - 1) : c.s_row[x];
 }
 
+// Loads are issued unconditionally: a block past the end of the wave's work (valid == false) re-reads the
+// chunk's first row instead (one cached row, no HBM traffic).  With the same sequence of memory
+// instructions on every path the compiler can count exactly how many younger loads may stay in flight when
+// an older block is consumed, which is what keeps the software pipeline full.
 template <int D>
-__device__ __forceinline__ void load_block(KVRegs<D> &r, const ChunkCtx &c, int x0) {
+__device__ __forceinline__ void load_block(KVRegs<D> &r, const ChunkCtx &c, int x0, bool valid) {
+    if (!valid) x0 = 0;
 #pragma unroll
     for (int aa = 0; aa < 2; ++aa) {
-        const uint16_t *kp = c.kbase + (size_t)tok_row(c, x0 + 16 * aa + c.n16) * c.row_stride;
+        const int rowk = valid ? tok_row(c, x0 + 16 * aa + c.n16) : c.begin0;
+        const uint16_t *kp = c.kbase + (size_t)rowk * c.row_stride;
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) r.k[aa][kk] = __builtin_bit_cast(bf16x8, load16(kp + 32 * kk));
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            r.v[4 * aa + i] = load16(c.vbase + (size_t)tok_row(c, x0 + 16 * aa + 4 * c.g + i) * c.row_stride);
+        for (int i = 0; i < 4; ++i) {
+            const int rowv = valid ? tok_row(c, x0 + 16 * aa + 4 * c.g + i) : c.begin0;
+            r.v[4 * aa + i] = load16(c.vbase + (size_t)rowv * c.row_stride);
+        }
     }
 }
 
@@ -231,62 +239,80 @@ template <int D>
 struct SplitPipe {
     KVRegs<D> b0, b1;
     __device__ __forceinline__ void prime(const ChunkCtx &ctx, int wave, int nblk) {
-        if (wave < nblk) load_block<D>(b0, ctx, wave * 32);
-        if (wave + kWaves < nblk) load_block<D>(b1, ctx, (wave + kWaves) * 32);
+        load_block<D>(b0, ctx, wave * 32, wave < nblk);
+        load_block<D>(b1, ctx, (wave + kWaves) * 32, wave + kWaves < nblk);
     }
     __device__ __forceinline__ void run(const ChunkCtx &ctx, int wave, int nblk, const bf16x8 (&qreg)[D / 32], int qpos,
                                         RowState &rs, f32x4 (&oacc)[8], float cs, float lazy) {
         for (int blk = wave; blk < nblk; blk += 2 * kWaves) {
             compute_block<D>(b0, ctx, blk * 32, qreg, qpos, rs, oacc, cs, lazy);
-            if (blk + 2 * kWaves < nblk) load_block<D>(b0, ctx, (blk + 2 * kWaves) * 32);
-            if (blk + kWaves < nblk) {
-                compute_block<D>(b1, ctx, (blk + kWaves) * 32, qreg, qpos, rs, oacc, cs, lazy);
-                if (blk + 3 * kWaves < nblk) load_block<D>(b1, ctx, (blk + 3 * kWaves) * 32);
-            }
+            load_block<D>(b0, ctx, (blk + 2 * kWaves) * 32, blk + 2 * kWaves < nblk);
+            if (blk + kWaves < nblk) compute_block<D>(b1, ctx, (blk + kWaves) * 32, qreg, qpos, rs, oacc, cs, lazy);
+            load_block<D>(b1, ctx, (blk + 3 * kWaves) * 32, blk + 3 * kWaves < nblk);
         }
     }
 };
 
 // ---- row-split path (groups of TR = 2 or 4 row tiles): the TR waves that work on the same blocks each
 //      fetch 1/TR of a block from HBM and pass it to the others through LDS, so the block is read once.
+// A block is 2*KK + 8 register images of 1 KB (K tile a, step kk -> image a*KK + kk; V token j -> image
+// 2*KK + j).  With TR = 2 wave t fetches K tile t and V tokens 4t..4t+3; with TR = 4 waves 0 and 1 fetch the
+// two K tiles and waves 2 and 3 four V tokens each.  Either way every 2*d-byte token row is read whole, by
+// one wave, in back-to-back loads.
 template <int D, int TR>
 struct Share {
     static constexpr int KK = D / 32;
-    static constexpr int H = TR / 2;       // waves per 16-token half of a block
-    static constexpr int NK = KK / H;      // 128-bit K loads of one wave per block
-    static constexpr int NV = 4 / H;       // 128-bit V loads of one wave per block
-    static constexpr int NSLOT = 2 * KK + 8;  // 1 KB register images per block (K then V)
-    u32x4 x[NK + NV];
+    static constexpr int NSLOT = 2 * KK + 8;
+    static constexpr int NX = TR == 2 ? KK + 4 : (KK > 4 ? KK : 4);
+    u32x4 x[NX];
 };
 
 template <int D, int TR>
-__device__ __forceinline__ void share_issue(Share<D, TR> &s, const ChunkCtx &c, int t, int x0) {
-    using S = Share<D, TR>;
-    const int am = t / S::H, hk = t % S::H;
-    const uint16_t *kp = c.kbase + (size_t)tok_row(c, x0 + 16 * am + c.n16) * c.row_stride;
+__device__ __forceinline__ void share_issue(Share<D, TR> &s, const ChunkCtx &c, int t, int x0, bool valid) {
+    constexpr int KK = D / 32;
+    if (!valid) x0 = 0;
+    if (TR == 2 || t < 2) {
+        const int rowk = valid ? tok_row(c, x0 + 16 * t + c.n16) : c.begin0;
+        const uint16_t *kp = c.kbase + (size_t)rowk * c.row_stride;
 #pragma unroll
-    for (int q = 0; q < S::NK; ++q) s.x[q] = load16(kp + 32 * (hk * S::NK + q));
+        for (int q = 0; q < KK; ++q) s.x[q] = load16(kp + 32 * q);
+    }
+    if (TR == 2) {
 #pragma unroll
-    for (int q = 0; q < S::NV; ++q)
-        s.x[S::NK + q] = load16(c.vbase + (size_t)tok_row(c, x0 + 16 * am + 4 * c.g + hk * S::NV + q) * c.row_stride);
+        for (int q = 0; q < 4; ++q) {
+            const int rowv = valid ? tok_row(c, x0 + 16 * t + 4 * c.g + q) : c.begin0;
+            s.x[KK + q] = load16(c.vbase + (size_t)rowv * c.row_stride);
+        }
+    } else if (t >= 2) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int rowv = valid ? tok_row(c, x0 + 16 * (t - 2) + 4 * c.g + q) : c.begin0;
+            s.x[q] = load16(c.vbase + (size_t)rowv * c.row_stride);
+        }
+    }
 }
 
 template <int D, int TR>
 __device__ __forceinline__ void share_step(Share<D, TR> &s, const ChunkCtx &c, u32x4 *xs, int t, int lane, int blk,
                                            int next_blk, int nblk, const bf16x8 (&qreg)[D / 32], int qpos,
                                            RowState &rs, f32x4 (&oacc)[8], float cs, float lazy) {
-    using S = Share<D, TR>;
     constexpr int KK = D / 32;
-    const int am = t / S::H, hk = t % S::H;
     const bool live = blk < nblk;
     if (live) {
+        if (TR == 2 || t < 2) {
 #pragma unroll
-        for (int q = 0; q < S::NK; ++q) xs[(am * KK + hk * S::NK + q) * 64 + lane] = s.x[q];
+            for (int q = 0; q < KK; ++q) xs[(t * KK + q) * 64 + lane] = s.x[q];
+        }
+        if (TR == 2) {
 #pragma unroll
-        for (int q = 0; q < S::NV; ++q) xs[(2 * KK + 4 * am + hk * S::NV + q) * 64 + lane] = s.x[S::NK + q];
+            for (int q = 0; q < 4; ++q) xs[(2 * KK + 4 * t + q) * 64 + lane] = s.x[KK + q];
+        } else if (t >= 2) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) xs[(2 * KK + 4 * (t - 2) + q) * 64 + lane] = s.x[q];
+        }
     }
     __syncthreads();
-    if (next_blk < nblk) share_issue<D, TR>(s, c, t, next_blk * 32);
+    share_issue<D, TR>(s, c, t, next_blk * 32, next_blk < nblk);
     if (live) {
         KVRegs<D> r;
 #pragma unroll
@@ -312,8 +338,7 @@ struct SharedPipe {
     __device__ __forceinline__ void prime(const ChunkCtx &ctx, int wave, int nblk) {
         const int t = wave % TR, part = wave / TR;
 #pragma unroll
-        for (int u = 0; u < DEPTH; ++u)
-            if (part + u * NP < nblk) share_issue<D, TR>(st[u], ctx, t, (part + u * NP) * 32);
+        for (int u = 0; u < DEPTH; ++u) share_issue<D, TR>(st[u], ctx, t, (part + u * NP) * 32, part + u * NP < nblk);
     }
     __device__ __forceinline__ void run(const ChunkCtx &ctx, u32x4 *xbuf, int wave, int lane, int nblk,
                                         const bf16x8 (&qreg)[D / 32], int qpos, RowState &rs, f32x4 (&oacc)[8],
@@ -321,17 +346,16 @@ struct SharedPipe {
         const int t = wave % TR, part = wave / TR;
         const int iters = (nblk + NP - 1) / NP;  // the same for every wave: barriers stay aligned
         u32x4 *xb = xbuf + (size_t)part * 2 * S::NSLOT * 64;
+        // whole rounds of DEPTH steps; steps past the last block only keep the barrier and a dummy load
         for (int it0 = 0; it0 < iters; it0 += DEPTH) {
 #pragma unroll
             for (int u = 0; u < DEPTH; ++u) {
                 const int it = it0 + u;
-                if (it < iters) {
-                    const int blk = part + it * NP;
-                    // LDS exchange stages alternate; stage (it & 1) was last read two steps ago, before the
-                    // barrier of the previous step
-                    share_step<D, TR>(st[u], ctx, xb + (it & 1) * S::NSLOT * 64, t, lane, blk, blk + DEPTH * NP, nblk,
-                                      qreg, qpos, rs, oacc, cs, lazy);
-                }
+                const int blk = part + it * NP;
+                // LDS exchange stages alternate; stage (it & 1) was last read two steps ago, before the
+                // barrier of the previous step
+                share_step<D, TR>(st[u], ctx, xb + (it & 1) * S::NSLOT * 64, t, lane, blk, blk + DEPTH * NP, nblk,
+                                  qreg, qpos, rs, oacc, cs, lazy);
             }
         }
     }
@@ -363,7 +387,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     const unsigned long long t_begin = wall_clock64();
 #endif
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the block loops on scalar branches
     const int n16 = lane & 15;
     const int g = lane >> 4;
 #ifdef DEFT_HEAD_MAJOR
@@ -434,25 +459,23 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
         __syncthreads();
     }
 
-    // ---- this wave's 16 rows; Q is the B operand, resident for the whole chunk.  It is fetched after the
-    //      first K/V loads have been issued so that its two dependent reads do not delay them.
+    // ---- this wave's 16 rows; Q is the B operand, resident for the whole chunk.  The query index is fetched
+    //      first, the first K/V blocks are put in flight while it travels, then Q itself is fetched; one full
+    //      wait before the main loop leaves nothing but the block pipeline outstanding inside it.
     const int my_tile = wave % TR;
-    int qpos = -1;
+    const int my_r = 16 * (tile0 + my_tile) + n16;
+    const bool row_ok = (my_tile < ntiles) && (my_r < R);
+    const int my_pl = my_r / a.G, my_gh = my_r - my_pl * a.G;
+    const int qpos = row_ok ? cqlo + my_pl : -1;
+    int q_user = 0;
+    if (row_ok) q_user = a.q_order[cqlo + my_pl];
     bf16x8 qreg[KK];
     auto load_q = [&]() {
-        const int r = 16 * (tile0 + my_tile) + n16;
-        const bool ok = (my_tile < ntiles) && (r < R);
-        const int pl = r / a.G, gh = r - pl * a.G;
         const u32x4 z = {0, 0, 0, 0};
+        const uint16_t *qp = a.q + ((size_t)q_user * a.Hq + (size_t)h * a.G + my_gh) * D + 8 * g;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) qreg[kk] = __builtin_bit_cast(bf16x8, z);
-        if (ok) {
-            qpos = cqlo + pl;
-            const int j = a.q_order[cqlo + pl];
-            const uint16_t *qp = a.q + ((size_t)j * a.Hq + (size_t)h * a.G + gh) * D + 8 * g;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) qreg[kk] = __builtin_bit_cast(bf16x8, load16(qp + 32 * kk));
-        }
+        for (int kk = 0; kk < KK; ++kk) qreg[kk] = __builtin_bit_cast(bf16x8, row_ok ? load16(qp + 32 * kk) : z);
+        __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0)
     };
 
     RowState rs = {-INFINITY, 0.f, 0.f};
@@ -466,33 +489,18 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
 #endif
     if (TR == 1) {
         SplitPipe<D> pipe;
-#ifndef DEFT_Q_LAST
-        load_q();
-        pipe.prime(ctx, wave, nblk);
-#else
         pipe.prime(ctx, wave, nblk);
         load_q();
-#endif
         pipe.run(ctx, wave, nblk, qreg, qpos, rs, oacc, a.c, lazy);
     } else if (TR == 2) {
         SharedPipe<D, 2> pipe;
-#ifndef DEFT_Q_LAST
-        load_q();
-        pipe.prime(ctx, wave, nblk);
-#else
         pipe.prime(ctx, wave, nblk);
         load_q();
-#endif
         pipe.run(ctx, xbuf, wave, lane, nblk, qreg, qpos, rs, oacc, a.c, lazy);
     } else {
         SharedPipe<D, 4> pipe;
-#ifndef DEFT_Q_LAST
-        load_q();
-        pipe.prime(ctx, wave, nblk);
-#else
         pipe.prime(ctx, wave, nblk);
         load_q();
-#endif
         pipe.run(ctx, xbuf, wave, lane, nblk, qreg, qpos, rs, oacc, a.c, lazy);
     }
 
