@@ -39,7 +39,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = few-shot, the headline)")
     ap.add_argument("--layers", type=int, default=32)
-    ap.add_argument("--chunk", type=int, default=0, help="S_t, tokens per chunk (0 = library default)")
+    ap.add_argument("--chunk", type=int, default=0,
+                    help="S_t, tokens per chunk (0 = deft_suggest_chunk_size for this tree; 128 = the paper's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="bound on the oracle timing loop")
     return ap.parse_args()
@@ -95,6 +96,9 @@ def main():
     qn = np.ascontiguousarray(tree.query_node, dtype=np.int32)
     nbp, nlp, parp, qnp = (a.ctypes.data_as(i32p) for a in (nb, nl, par, qn))
 
+    if args.chunk == 0:
+        args.chunk = binding.deft_suggest_chunk_size(nl, par, qn, Hq, Hkv)
+
     # sizes are a property of the tree: allocate the image buffer and the workspace once
     probe = binding.deft_plan(nb, nl, par, qn, tree.ntok, args.chunk)
     view = probe.view()
@@ -115,6 +119,8 @@ def main():
 
     def prepare():
         h = vp()
+        if lib.deft_suggest_chunk_size(nlp, parp, tree.n_nodes, qnp, tree.nq, Hq, Hkv) < 0:
+            raise RuntimeError("deft_suggest_chunk_size failed")
         check(lib.deft_plan(nbp, nlp, parp, tree.n_nodes, qnp, tree.nq, tree.ntok, args.chunk, 0, ctypes.byref(h)),
               "deft_plan")
         if lib.deft_plan_device_bytes(h, Hq, Hkv) > img_bytes:
@@ -141,6 +147,7 @@ def main():
     t1 = time.perf_counter()
     step_s = (t1 - t0) / max(args.steps, 1)
     us_per_call = step_s * 1e6 / L
+    out_layer0 = outs[0].float().cpu().numpy().astype(np.float64)  # taken before the per-stage pass reuses the workspace
 
     # host cost of the preparation phase alone
     tp0 = time.perf_counter()
@@ -216,8 +223,7 @@ def main():
             if time.perf_counter() - tc0 >= args.cpu_seconds:
                 break
         cpu_us = (time.perf_counter() - tc0) / reps * 1e6
-        got = outs[0].float().cpu().numpy().astype(np.float64)
-        err = float(np.abs(got - ref).max())
+        err = float(np.abs(out_layer0 - ref).max())
         result["cpu_baseline"] = {
             "value": round(cpu_us, 1), "unit": "us/layer-call", "cores": used, "kind": "oracle",
             "sample": f"one full layer-call of {workload} (fp64, all {tree.nq}x{Hq} query rows), mean of {reps} runs",

@@ -66,8 +66,12 @@ def chunk_tokens(plan, c):
     return np.asarray(rows, dtype=np.int64)
 
 
-def attention_by_plan(plan, Q, K, V, scale=None):
-    """Two-stage DeFT-Flatten attention; Q [nq,Hq,d], K/V [ntok,Hkv,d] -> O [nq,Hq,d] (fp64)."""
+def partials_by_plan(plan, Q, K, V, scale=None):
+    """Stage 1 of Algorithm 4: per QKV group the masked partial attention o_i and LogSumExp lse_i.
+
+    Returns (part_o [n_slots,Hq,d], part_lse [n_slots,Hq]); a (slot, head) whose query sees no token of
+    the chunk keeps lse = -inf and o = 0.
+    """
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
@@ -80,8 +84,6 @@ def attention_by_plan(plan, Q, K, V, scale=None):
     n_slots = int(plan["n_slots"])
     part_o = np.zeros((n_slots, Hq, d))
     part_lse = np.full((n_slots, Hq), -np.inf)
-
-    # stage 1: one partial attention per QKV group
     for c in range(int(plan["n_chunks"])):
         lo, hi = int(plan["chunk_qlo"][c]), int(plan["chunk_qhi"][c])
         rows = chunk_tokens(plan, c)
@@ -99,7 +101,16 @@ def attention_by_plan(plan, Q, K, V, scale=None):
                 e = np.exp(S[j] - smax)
                 part_lse[base + j, h] = smax + np.log(e.sum())
                 part_o[base + j, h] = (e / e.sum()) @ Vb
+    return part_o, part_lse
 
+
+def attention_by_plan(plan, Q, K, V, scale=None):
+    """Two-stage DeFT-Flatten attention; Q [nq,Hq,d], K/V [ntok,Hkv,d] -> O [nq,Hq,d] (fp64)."""
+    Q = np.asarray(Q, dtype=np.float64)
+    nq, Hq, d = Q.shape
+    q_order = plan["q_order"]
+    # stage 1: one partial attention per QKV group
+    part_o, part_lse = partials_by_plan(plan, Q, K, V, scale)
     # stage 2: tree-topology-aware global reduction, per query
     O = np.zeros((nq, Hq, d))
     for p in range(nq):

@@ -21,7 +21,7 @@ DEFT_OUT_BF16 = 0
 DEFT_OUT_F32 = 1
 
 EXPORTS = (
-    "deft_plan", "deft_plan_view", "deft_plan_device_bytes", "deft_plan_upload", "deft_workspace_bytes",
+    "deft_plan", "deft_suggest_chunk_size", "deft_plan_view", "deft_plan_device_bytes", "deft_plan_upload", "deft_workspace_bytes",
     "deft_tree_attn_decode", "deft_stage1_partial_attention", "deft_stage2_global_reduction",
     "deft_plan_destroy", "deft_strerror", "deft_last_hip_error",
 )
@@ -78,6 +78,8 @@ def load_library():
     vp, c32, csz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     lib.deft_plan.restype = ctypes.c_int
     lib.deft_plan.argtypes = [_i32p, _i32p, _i32p, c32, _i32p, c32, c32, c32, ctypes.c_uint32, ctypes.POINTER(vp)]
+    lib.deft_suggest_chunk_size.restype = ctypes.c_int32
+    lib.deft_suggest_chunk_size.argtypes = [_i32p, _i32p, c32, _i32p, c32, c32, c32]
     lib.deft_plan_view.restype = ctypes.c_int
     lib.deft_plan_view.argtypes = [vp, ctypes.POINTER(_PlanView)]
     lib.deft_plan_device_bytes.restype = csz
@@ -193,6 +195,17 @@ def _stream_ptr(stream, device):
     if stream is None:
         stream = torch.cuda.current_stream(device)
     return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def deft_suggest_chunk_size(node_tok_len, node_parent, query_node, Hq: int, Hkv: int) -> int:
+    """Chunk size S_t that gives about two equal stage-1 tasks per compute unit for this tree."""
+    nl, par, qn = _i32(node_tok_len), _i32(node_parent), _i32(query_node)
+    qptr = qn.ctypes.data_as(_i32p) if qn.size else None
+    rc = load_library().deft_suggest_chunk_size(nl.ctypes.data_as(_i32p), par.ctypes.data_as(_i32p), nl.size, qptr,
+                                                qn.size, int(Hq), int(Hkv))
+    if rc < 0:
+        _check(rc, "deft_suggest_chunk_size")
+    return int(rc)
 
 
 def deft_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok: int, chunk_size: int = 0,

@@ -60,7 +60,13 @@ struct Stage2Args {
     float c;
 };
 
-__device__ __forceinline__ u32x4 load16(const uint16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
+__device__ __forceinline__ u32x4 load16(const uint16_t *p) {
+#ifdef DEFT_NT_LOADS
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+#else
+    return *reinterpret_cast<const u32x4 *>(p);
+#endif
+}
 
 __device__ __forceinline__ float wave_row_max(float x) {
     // a row of a 16-row tile lives in lanes {n, n+16, n+32, n+48}
@@ -573,7 +579,11 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
         t[0] = t_begin;
         t[1] = t_pro;
         t[2] = t_loop;
-        t[3] = wall_clock64();
+        // low 40 bits: end time; high bits: HW_ID (reg 4) and XCC_ID (reg 20) for placement studies
+        const unsigned hw = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));
+        const unsigned xcc = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (3 << 11));
+        t[3] = (wall_clock64() & 0xffffffffffull) | ((unsigned long long)(hw & 0xffff) << 40) |
+               ((unsigned long long)(xcc & 0xf) << 56);
     }
 #endif
 }

@@ -212,6 +212,46 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
     }
 }
 
+// Chunk size that fills an MI355X once.  Stage 1 runs one workgroup per (chunk, KV head, 64 rows of the
+// chunk's group) and the chip holds two such workgroups on each of its 256 compute units; since a compute
+// unit streams at a fixed rate however many workgroups it holds, the kernel is fastest when every unit
+// gets the same number of bytes, i.e. when there are about 512 equal tasks.  The estimate weighs each
+// reached node's tokens by the number of 64-row tasks its own query group needs.
+extern "C" int32_t deft_suggest_chunk_size(const int32_t *node_tok_len, const int32_t *node_parent, int32_t n_nodes,
+                                           const int32_t *query_node, int32_t nq, int32_t Hq, int32_t Hkv) {
+    if (!node_tok_len || !node_parent || n_nodes < 1 || nq < 0 || (nq > 0 && !query_node)) return DEFT_EINVAL;
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return DEFT_EINVAL;
+    try {
+        for (int32_t u = 0; u < n_nodes; ++u)
+            if (node_parent[u] < -1 || node_parent[u] >= n_nodes || node_parent[u] == u || node_tok_len[u] < 0)
+                return DEFT_EINVAL;
+        for (int32_t j = 0; j < nq; ++j)
+            if (query_node[j] < 0 || query_node[j] >= n_nodes) return DEFT_EINVAL;
+        std::vector<int32_t> pre, fc, ns;
+        if (!preorder(node_parent, n_nodes, pre, fc, ns)) return DEFT_EINVAL;
+        std::vector<int64_t> sub(n_nodes, 0);
+        for (int32_t j = 0; j < nq; ++j) ++sub[query_node[j]];
+        for (int32_t i = n_nodes - 1; i >= 0; --i) {
+            const int32_t u = pre[i], p = node_parent[u];
+            if (p >= 0) sub[p] += sub[u];
+        }
+        const int64_t G = Hq / Hkv;
+        long double task_tokens = 0;
+        for (int32_t u = 0; u < n_nodes; ++u) {
+            if (sub[u] == 0) continue;
+            const int64_t row_groups = (sub[u] * G + 63) / 64;
+            task_tokens += (long double)node_tok_len[u] * (long double)row_groups;
+        }
+        const long double per_task = task_tokens * Hkv / 512.0L;
+        // a multiple of 128 tokens = 4 waves x 32-token blocks, so a token-split task gives every wave the same work
+        int64_t chunk = ((int64_t)per_task + 127) / 128 * 128;
+        chunk = std::max<int64_t>(128, std::min<int64_t>(1024, chunk));
+        return (int32_t)chunk;
+    } catch (...) {
+        return DEFT_ENOMEM;
+    }
+}
+
 extern "C" int deft_plan_view(const deft_plan_t *P, deft_plan_view_t *out) {
     if (!P || !out) return DEFT_EINVAL;
     out->chunk_size = P->chunk_size;

@@ -68,6 +68,57 @@ def test_benchmark_configs_match_oracle(cfg):
         assert np.array_equal(view[key], want[key]), key
 
 
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_benchmark_configs_at_the_chunk_size_bench_uses(cfg):
+    t = wl.make_config(cfg)
+    chunk = binding.deft_suggest_chunk_size(t.node_tok_len, t.node_parent, t.query_node, t.Hq, t.Hkv)
+    print(f"\n  config {cfg} at suggested chunk {chunk}", flush=True)
+    Q, K, V = wl.make_qkv(t)
+    got, _ = run_gpu(t, Q, K, V, chunk_size=chunk)
+    check(got, reference(t, Q, K, V), strict=True)
+
+
+def test_stage1_partials_match_algorithm4_and_stage2_completes_them():
+    # stage 1 alone, in the paper's notation: LSE_i = scale*m + ln(l), PA_i = acc / l per (slot, head)
+    from oracle import deft_flatten
+
+    t = wl.random_tree(7, n_nodes=11, max_len=90, nq=21, Hq=8, Hkv=2, d=128, n_roots=2)
+    Q, K, V = wl.make_qkv(t)
+    dev = torch.device("cuda:0")
+    plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, 64)
+    lib = binding.load_library()
+    q, k, v = Q.to(dev), K.to(dev), V.to(dev)
+    img = plan.image(t.Hq, t.Hkv, dev)
+    ws = plan.workspace(t.Hq, t.Hkv, t.d, dev)
+    ws.zero_()
+    st = torch.cuda.current_stream().cuda_stream
+    rc = lib.deft_stage1_partial_attention(plan.handle, img.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                           t.Hq, t.Hkv, t.d, 0.0, ws.data_ptr(), ws.numel(), st)
+    assert rc == 0
+    torch.cuda.synchronize()
+    view = plan.view()
+    rows = view["n_slots"] * t.Hq
+    wsf = ws.view(torch.float32).cpu().numpy().astype(np.float64)
+    acc = wsf[:rows * t.d].reshape(view["n_slots"], t.Hq, t.d)
+    m = wsf[rows * t.d:rows * t.d + rows].reshape(view["n_slots"], t.Hq)
+    l = wsf[rows * t.d + rows:rows * t.d + 2 * rows].reshape(view["n_slots"], t.Hq)
+    want_o, want_lse = deft_flatten.partials_by_plan(view, Q.float().numpy(), K.float().numpy(), V.float().numpy())
+    seen = np.isfinite(want_lse)
+    assert np.array_equal(seen, l > 0)
+    scale = 1.0 / np.sqrt(t.d)
+    lse = scale * m[seen] + np.log(l[seen])
+    assert np.abs(lse - want_lse[seen]).max() <= 2e-3
+    pa = acc[seen] / l[seen][:, None]
+    assert (np.abs(pa - want_o[seen]) <= ABS_TOL + REL_TOL * np.abs(want_o[seen])).all()
+    # stage 2 on those partials gives the attention
+    o = torch.empty((t.nq, t.Hq, t.d), dtype=torch.float32, device=dev)
+    rc = lib.deft_stage2_global_reduction(plan.handle, img.data_ptr(), o.data_ptr(), t.Hq, t.Hkv, t.d, 0.0, 1,
+                                          ws.data_ptr(), ws.numel(), st)
+    assert rc == 0
+    torch.cuda.synchronize()
+    check(o.cpu().numpy().astype(np.float64), reference(t, Q, K, V), strict=False)
+
+
 def test_tiny_variant_with_320_tokens():
     t = wl.config1_tiny(leaf_len=16)
     Q, K, V = wl.make_qkv(t)

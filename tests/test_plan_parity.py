@@ -121,3 +121,21 @@ def test_large_chain_is_planned_quickly():
     beg = (np.arange(n, dtype=np.int64) * 3).astype(np.int32)
     v = binding.deft_plan(beg, lens, par, [n - 1, n // 2], 3 * n, 128).view()
     assert v["n_flat"] == 3 * n and v["n_chunks"] == -(-3 * n // 128)
+
+
+def test_suggested_chunk_size():
+    for cfg in range(1, 6):
+        t = wl.make_config(cfg)
+        c = binding.deft_suggest_chunk_size(t.node_tok_len, t.node_parent, t.query_node, t.Hq, t.Hkv)
+        assert 128 <= c <= 1024 and c % 128 == 0
+        assert_same_plan(t, c)     # whatever it suggests, the plan is still the oracle's plan
+    # few-shot: about 512 tasks of (chunk, KV head)
+    t = wl.make_config(2)
+    c = binding.deft_suggest_chunk_size(t.node_tok_len, t.node_parent, t.query_node, t.Hq, t.Hkv)
+    assert 400 <= -(-t.ntok // c) * t.Hkv <= 512
+    with pytest.raises(binding.DeftError):
+        binding.deft_suggest_chunk_size([4, 4], [1, 0], [1], 4, 2)      # cycle
+    with pytest.raises(binding.DeftError):
+        binding.deft_suggest_chunk_size([4, 4], [-1, 0], [1], 4, 3)     # Hq % Hkv != 0
+    with pytest.raises(binding.DeftError):
+        binding.deft_suggest_chunk_size([4, 4], [-1, 0], [7], 4, 2)     # query node out of range
