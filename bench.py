@@ -42,13 +42,16 @@ def parse_args():
     ap.add_argument("--chunk", type=int, default=0,
                     help="S_t, tokens per chunk (0 = deft_suggest_chunk_size for this tree; 128 = the paper's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a few plain 1 GiB device-to-device copies (known size) so that a rocprofv3 "
+                         "--pmc run of this command can scale its FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="bound on the oracle timing loop")
     return ap.parse_args()
 
 
 def traffic_from_profiles(workload: str):
     """HBM bytes per stage-1 launch measured with rocprofv3 --pmc, if a committed summary states it."""
-    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    path = os.path.join(ROOT, "profiles", "stage1_%s_hbm_traffic.txt" % workload)
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -73,6 +76,14 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     lib = binding.load_library()
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     tree = workloads.make_config(args.config)
     Hq, Hkv, d, L = tree.Hq, tree.Hkv, tree.d, args.layers
