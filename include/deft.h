@@ -118,7 +118,7 @@ int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_len, const 
 
 /*
  * A chunk size S_t suited to this tree on an MI355X (the paper leaves S_t as a tuning knob, Fig. 11):
- * the multiple of 128 in [128, 1024] that makes the number of stage-1 tasks, (chunk, KV head, 64 rows of
+ * the multiple of 128 in [128, 1024] that makes the number of stage-1 tasks, (chunk, KV head, 128 rows of
  * the chunk's query group), about twice the number of compute units, so that every unit streams the
  * same number of KV bytes.  Host arrays as for deft_plan (token begins are not needed).  Returns the
  * size, or a negative deft_status on malformed input.  Any valid S_t gives the same attention result.

@@ -149,22 +149,35 @@ struct RowState {
 };
 constexpr float kLazyLog2 = 8.0f;
 
-// Online-softmax step of one wave over one 32-token block, for its 16-row tile.
+// Everything a wave keeps for one of its 16-row tiles: Q as the B operand of S^T = K Q^T (resident for the
+// whole chunk), the plan position of this lane's row (-1: no such row), the softmax state and the O^T
+// accumulators (oacc[c'][i] is d = 32g + 8i + c' of row n16).
 template <int D>
-__device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx &c, int x0,
-                                              const bf16x8 (&qreg)[D / 32], const int qpos, RowState &st,
-                                              f32x4 (&oacc)[8], const float cs, const float lazy) {
+struct TileState {
+    bf16x8 q[D / 32];
+    int qpos;
+    RowState rs;
+    f32x4 o[8];
+};
+
+// Online-softmax step of one wave over one 32-token block, for its NT row tiles.  The K and V operands are
+// shared by the tiles, so the loads (or LDS reads) and the V interleave are paid once per block.
+template <int D, int NT>
+__device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx &c, int x0, TileState<D> (&ts)[NT],
+                                              const float cs, const float lazy) {
     constexpr int KK = D / 32;
-    // S^T = K Q^T : sacc[a][i] is the score of token 16a + 4g + i against row n16
-    f32x4 sacc[2];
+    // S^T = K Q^T : sacc[t][a][i] is the score of token 16a + 4g + i against row n16 of tile t
+    f32x4 sacc[NT][2];
 #pragma unroll
-    for (int aa = 0; aa < 2; ++aa) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int aa = 0; aa < 2; ++aa)
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.k[aa][kk], qreg[kk], acc, 0, 0, 0);
-        sacc[aa] = acc;
-    }
+        for (int t = 0; t < NT; ++t) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.k[aa][kk], ts[t].q[kk], acc, 0, 0, 0);
+            sacc[t][aa] = acc;
+        }
 
     // mask: a token is visible to plan position qpos iff qlo <= qpos < qhi of the node piece it belongs to.
     // A full block of a single-piece chunk is visible to every row of the chunk's group: nothing to mask
@@ -186,40 +199,48 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
                 qhi = *reinterpret_cast<const i32x4 *>(&c.s_qhi[xv]);
             }
 #pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool on = (ts[t].qpos >= qlo[i]) && (ts[t].qpos < qhi[i]);
+                    sacc[t][aa][i] = on ? sacc[t][aa][i] : -INFINITY;
+                }
+        }
+    }
+
+    bf16x8 preg[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        RowState &st = ts[t].rs;
+        float mx = fmaxf(fmaxf(fmaxf(sacc[t][0][0], sacc[t][0][1]), fmaxf(sacc[t][0][2], sacc[t][0][3])),
+                         fmaxf(fmaxf(sacc[t][1][0], sacc[t][1][1]), fmaxf(sacc[t][1][2], sacc[t][1][3])));
+        if (__any(mx > st.m + lazy)) {
+            // raise the reference of every row to its exact running maximum and rescale what was accumulated
+            mx = wave_row_max(mx);
+            const float m_new = fmaxf(st.m, mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(st.m * cs - m_use * cs);  // exp2(-inf) = 0 on the first raise
+            st.m = m_new;
+            st.mc = m_use * cs;
+            st.l *= alpha;
+#pragma unroll
+            for (int cc = 0; cc < 8; ++cc) ts[t].o[cc] *= alpha;
+        }
+        float pv[8];
+        float psum = 0.f;
+#pragma unroll
+        for (int aa = 0; aa < 2; ++aa)
+#pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const bool on = (qpos >= qlo[i]) && (qpos < qhi[i]);
-                sacc[aa][i] = on ? sacc[aa][i] : -INFINITY;
+                const float e = __builtin_amdgcn_exp2f(fmaf(sacc[t][aa][i], cs, -st.mc));
+                pv[4 * aa + i] = e;
+                psum += e;
             }
-        }
+        st.l += psum;
+        const u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]),
+                          pack_bf16(pv[6], pv[7])};
+        preg[t] = __builtin_bit_cast(bf16x8, pk);
     }
-    float mx = fmaxf(fmaxf(fmaxf(sacc[0][0], sacc[0][1]), fmaxf(sacc[0][2], sacc[0][3])),
-                     fmaxf(fmaxf(sacc[1][0], sacc[1][1]), fmaxf(sacc[1][2], sacc[1][3])));
-    if (__any(mx > st.m + lazy)) {
-        // raise the reference of every row to its exact running maximum and rescale what was accumulated
-        mx = wave_row_max(mx);
-        const float m_new = fmaxf(st.m, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(st.m * cs - m_use * cs);  // exp2(-inf) = 0 on the first raise
-        st.m = m_new;
-        st.mc = m_use * cs;
-        st.l *= alpha;
-#pragma unroll
-        for (int cc = 0; cc < 8; ++cc) oacc[cc] *= alpha;
-    }
-    float pv[8];
-    float psum = 0.f;
-#pragma unroll
-    for (int aa = 0; aa < 2; ++aa)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float e = __builtin_amdgcn_exp2f(fmaf(sacc[aa][i], cs, -st.mc));
-            pv[4 * aa + i] = e;
-            psum += e;
-        }
-    st.l += psum;
-    const u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]),
-                      pack_bf16(pv[6], pv[7])};
-    const bf16x8 preg = __builtin_bit_cast(bf16x8, pk);
 
     // O^T += V^T P^T.  The V^T operand of product c' = 2*c2 + {0,1} is a 16-bit interleave of token pairs:
     // vt[p] = {V[tok 2p][8*n16 + c'], V[tok 2p+1][8*n16 + c']}
@@ -232,10 +253,13 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
             vt_lo[p] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
             vt_hi[p] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
         }
-        oacc[2 * c2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt_lo), preg,
-                                                                oacc[2 * c2], 0, 0, 0);
-        oacc[2 * c2 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt_hi), preg,
-                                                                    oacc[2 * c2 + 1], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            ts[t].o[2 * c2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt_lo), preg[t],
+                                                                       ts[t].o[2 * c2], 0, 0, 0);
+            ts[t].o[2 * c2 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt_hi), preg[t],
+                                                                           ts[t].o[2 * c2 + 1], 0, 0, 0);
+        }
     }
 }
 
@@ -248,12 +272,12 @@ struct SplitPipe {
         load_block<D>(b0, ctx, wave * 32, wave < nblk);
         load_block<D>(b1, ctx, (wave + kWaves) * 32, wave + kWaves < nblk);
     }
-    __device__ __forceinline__ void run(const ChunkCtx &ctx, int wave, int nblk, const bf16x8 (&qreg)[D / 32], int qpos,
-                                        RowState &rs, f32x4 (&oacc)[8], float cs, float lazy) {
+    __device__ __forceinline__ void run(const ChunkCtx &ctx, int wave, int nblk, TileState<D> (&ts)[1], float cs,
+                                        float lazy) {
         for (int blk = wave; blk < nblk; blk += 2 * kWaves) {
-            compute_block<D>(b0, ctx, blk * 32, qreg, qpos, rs, oacc, cs, lazy);
+            compute_block<D, 1>(b0, ctx, blk * 32, ts, cs, lazy);
             load_block<D>(b0, ctx, (blk + 2 * kWaves) * 32, blk + 2 * kWaves < nblk);
-            if (blk + kWaves < nblk) compute_block<D>(b1, ctx, (blk + kWaves) * 32, qreg, qpos, rs, oacc, cs, lazy);
+            if (blk + kWaves < nblk) compute_block<D, 1>(b1, ctx, (blk + kWaves) * 32, ts, cs, lazy);
             load_block<D>(b1, ctx, (blk + 3 * kWaves) * 32, blk + 3 * kWaves < nblk);
         }
     }
@@ -298,10 +322,9 @@ __device__ __forceinline__ void share_issue(Share<D, TR> &s, const ChunkCtx &c, 
     }
 }
 
-template <int D, int TR>
+template <int D, int TR, int NT>
 __device__ __forceinline__ void share_step(Share<D, TR> &s, const ChunkCtx &c, u32x4 *xs, int t, int lane, int blk,
-                                           int next_blk, int nblk, const bf16x8 (&qreg)[D / 32], int qpos,
-                                           RowState &rs, f32x4 (&oacc)[8], float cs, float lazy) {
+                                           int next_blk, int nblk, TileState<D> (&ts)[NT], float cs, float lazy) {
     constexpr int KK = D / 32;
     const bool live = blk < nblk;
     if (live) {
@@ -327,19 +350,19 @@ __device__ __forceinline__ void share_step(Share<D, TR> &s, const ChunkCtx &c, u
             for (int kk = 0; kk < KK; ++kk) r.k[aa][kk] = __builtin_bit_cast(bf16x8, xs[(aa * KK + kk) * 64 + lane]);
 #pragma unroll
         for (int j = 0; j < 8; ++j) r.v[j] = xs[(2 * KK + j) * 64 + lane];
-        compute_block<D>(r, c, blk * 32, qreg, qpos, rs, oacc, cs, lazy);
+        compute_block<D, NT>(r, c, blk * 32, ts, cs, lazy);
     }
 }
 
-template <int D, int TR>
+// NT = row tiles per wave.  A block read back from LDS serves all NT tiles of the wave: with one tile per
+// wave the four waves of a workgroup pull 4 x 16 KB through LDS per block, twice what the MFMAs of the block
+// take, so groups wider than four tiles run two tiles per wave (LDS and MFMA time then balance).
+template <int D, int TR, int NT>
 struct SharedPipe {
     using S = Share<D, TR>;
     static constexpr int NP = kWaves / TR;  // token parts: part p takes blocks p, p+NP, ...
-#ifndef DEFT_DEPTH_NUM
-#define DEFT_DEPTH_NUM 2
-#endif
-    static constexpr int DEPTH = DEFT_DEPTH_NUM * TR / 2;  // blocks whose shares a wave keeps in flight (3/4 of the
-                                              // token-split path's bytes; the operands read back from LDS need the rest)
+    // blocks whose shares a wave keeps in flight; the two-tile variant has fewer registers to spare
+    static constexpr int DEPTH = NT == 1 ? TR : 2;
     Share<D, TR> st[DEPTH];
     __device__ __forceinline__ void prime(const ChunkCtx &ctx, int wave, int nblk) {
         const int t = wave % TR, part = wave / TR;
@@ -347,8 +370,7 @@ struct SharedPipe {
         for (int u = 0; u < DEPTH; ++u) share_issue<D, TR>(st[u], ctx, t, (part + u * NP) * 32, part + u * NP < nblk);
     }
     __device__ __forceinline__ void run(const ChunkCtx &ctx, u32x4 *xbuf, int wave, int lane, int nblk,
-                                        const bf16x8 (&qreg)[D / 32], int qpos, RowState &rs, f32x4 (&oacc)[8],
-                                        float cs, float lazy) {
+                                        TileState<D> (&ts)[NT], float cs, float lazy) {
         const int t = wave % TR, part = wave / TR;
         const int iters = (nblk + NP - 1) / NP;  // the same for every wave: barriers stay aligned
         u32x4 *xb = xbuf + (size_t)part * 2 * S::NSLOT * 64;
@@ -360,17 +382,19 @@ struct SharedPipe {
                 const int blk = part + it * NP;
                 // LDS exchange stages alternate; stage (it & 1) was last read two steps ago, before the
                 // barrier of the previous step
-                share_step<D, TR>(st[u], ctx, xb + (it & 1) * S::NSLOT * 64, t, lane, blk, blk + DEPTH * NP, nblk,
-                                  qreg, qpos, rs, oacc, cs, lazy);
+                share_step<D, TR, NT>(st[u], ctx, xb + (it & 1) * S::NSLOT * 64, t, lane, blk, blk + DEPTH * NP, nblk,
+                                      ts, cs, lazy);
             }
         }
     }
 };
 
-// Stage 1: one workgroup of four waves per task = (chunk, KV head, up to 64 rows of the chunk's group).
-// The rows are (query of the group) x (query head reading this KV head), tiled 16 at a time.  A task with
-// TR row tiles gives wave w tile w % TR and token part w / TR; the parts' partial results are merged in
-// LDS, so one (m, l, acc) triple per (chunk, row) reaches the workspace.
+// Stage 1: one workgroup of four waves per task = (chunk, KV head, up to 128 rows of the chunk's group).
+// The rows are (query of the group) x (query head reading this KV head), tiled 16 at a time.  A task of
+// 1, 2 or 3-4 tiles splits its rows over TR = 1, 2 or 4 waves and its tokens over the 4 / TR parts that
+// remain: wave w works on tile w % TR and token part w / TR.  A task of 5-8 tiles gives every wave two
+// tiles.  The parts' partial results are merged in LDS, so one (m, l, acc) triple per (chunk, row)
+// reaches the workspace.
 template <int D>
 __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     constexpr int KK = D / 32;  // k-steps of the Q.K^T contraction
@@ -411,7 +435,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     const int R = it[deft::kItWidth] * a.G;
     const int slot_base = it[deft::kItSlotBase];
     const int clen = it[deft::kItLen];
-    const int TR = ntiles <= 1 ? 1 : (ntiles == 2 ? 2 : 4);
+    const int TR = ntiles <= 1 ? 1 : (ntiles == 2 ? 2 : 4);  // waves that split the rows; 4 / TR token parts
 
     ChunkCtx ctx;
     ctx.row_stride = (size_t)a.Hkv * D;
@@ -465,30 +489,41 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
         __syncthreads();
     }
 
-    // ---- this wave's 16 rows; Q is the B operand, resident for the whole chunk.  The query index is fetched
-    //      first, the first K/V blocks are put in flight while it travels, then Q itself is fetched; one full
-    //      wait before the main loop leaves nothing but the block pipeline outstanding inside it.
-    const int my_tile = wave % TR;
-    const int my_r = 16 * (tile0 + my_tile) + n16;
-    const bool row_ok = (my_tile < ntiles) && (my_r < R);
-    const int my_pl = my_r / a.G, my_gh = my_r - my_pl * a.G;
-    const int qpos = row_ok ? cqlo + my_pl : -1;
-    int q_user = 0;
-    if (row_ok) q_user = a.q_order[cqlo + my_pl];
-    bf16x8 qreg[KK];
-    auto load_q = [&]() {
-        const u32x4 z = {0, 0, 0, 0};
-        const uint16_t *qp = a.q + ((size_t)q_user * a.Hq + (size_t)h * a.G + my_gh) * D + 8 * g;
+    // ---- this wave's rows: tile (wave % TR) of the task and, for tasks of more than four tiles, tile
+    //      (wave % TR) + 4 as well.  Q is the B operand, resident for the whole chunk.  The query indices are
+    //      fetched first, the first K/V blocks are put in flight while they travel, then Q itself is fetched;
+    //      one full wait before the main loop leaves nothing but the block pipeline outstanding inside it.
+    const int NTW = ntiles > 4 ? 2 : 1;  // tiles per wave
+    TileState<D> ts[2];
+    int q_user[2], q_head[2];
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) qreg[kk] = __builtin_bit_cast(bf16x8, row_ok ? load16(qp + 32 * kk) : z);
+    for (int u = 0; u < 2; ++u) {
+        const int tile = wave % TR + 4 * u;
+        const int r = 16 * (tile0 + tile) + n16;
+        const bool ok = (u < NTW) && (tile < ntiles) && (r < R);
+        const int pl = r / a.G;
+        q_head[u] = r - pl * a.G;
+        ts[u].qpos = ok ? cqlo + pl : -1;
+        q_user[u] = 0;
+        if (ok) q_user[u] = a.q_order[cqlo + pl];
+        ts[u].rs = RowState{-INFINITY, 0.f, 0.f};
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) ts[u].o[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    auto load_q = [&](int ntw) {
+        const u32x4 z = {0, 0, 0, 0};
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (u >= ntw) break;
+            const uint16_t *qp = a.q + ((size_t)q_user[u] * a.Hq + (size_t)h * a.G + q_head[u]) * D + 8 * g;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
+                ts[u].q[kk] = __builtin_bit_cast(bf16x8, ts[u].qpos >= 0 ? load16(qp + 32 * kk) : z);
+        }
         __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0)
     };
-
-    RowState rs = {-INFINITY, 0.f, 0.f};
     const float lazy = kLazyLog2 / a.c;
-    f32x4 oacc[8];
-#pragma unroll
-    for (int cc = 0; cc < 8; ++cc) oacc[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+    TileState<D>(&ts1)[1] = reinterpret_cast<TileState<D>(&)[1]>(ts);  // the one-tile paths use ts[0] only
 
 #ifdef DEFT_TRACE
     const unsigned long long t_pro = wall_clock64();
@@ -496,82 +531,94 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     if (TR == 1) {
         SplitPipe<D> pipe;
         pipe.prime(ctx, wave, nblk);
-        load_q();
-        pipe.run(ctx, wave, nblk, qreg, qpos, rs, oacc, a.c, lazy);
+        load_q(1);
+        pipe.run(ctx, wave, nblk, ts1, a.c, lazy);
     } else if (TR == 2) {
-        SharedPipe<D, 2> pipe;
+        SharedPipe<D, 2, 1> pipe;
         pipe.prime(ctx, wave, nblk);
-        load_q();
-        pipe.run(ctx, xbuf, wave, lane, nblk, qreg, qpos, rs, oacc, a.c, lazy);
+        load_q(1);
+        pipe.run(ctx, xbuf, wave, lane, nblk, ts1, a.c, lazy);
+    } else if (NTW == 1) {
+        SharedPipe<D, 4, 1> pipe;
+        pipe.prime(ctx, wave, nblk);
+        load_q(1);
+        pipe.run(ctx, xbuf, wave, lane, nblk, ts1, a.c, lazy);
     } else {
-        SharedPipe<D, 4> pipe;
+        SharedPipe<D, 4, 2> pipe;
         pipe.prime(ctx, wave, nblk);
-        load_q();
-        pipe.run(ctx, xbuf, wave, lane, nblk, qreg, qpos, rs, oacc, a.c, lazy);
+        load_q(2);
+        pipe.run(ctx, xbuf, wave, lane, nblk, ts, a.c, lazy);
     }
 
 #ifdef DEFT_TRACE
     const unsigned long long t_loop = wall_clock64();
 #endif
     // ---- merge the token parts in LDS and write one partial result per (chunk, row):
-    //      m = running maximum of the raw scores, l = sum of exp, acc = un-normalised weighted values
-    const float l_tot = wave_row_sum(rs.l);
-    __syncthreads();  // the exchange buffer is dead from here on; the merge buffer takes its place
-    if (g == 0) {
-        mM[wave * 16 + n16] = rs.m;
-        mL[wave * 16 + n16] = l_tot;
-    }
-    if (D == 128 || g < 2) {
-        // this lane owns d in [32g, 32g+32) of row n16: d = 32g + 8i + c'
-        float *dst = mO + (wave * 16 + n16) * OP + 32 * g;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const f32x4 lo4 = {oacc[0][i], oacc[1][i], oacc[2][i], oacc[3][i]};
-            const f32x4 hi4 = {oacc[4][i], oacc[5][i], oacc[6][i], oacc[7][i]};
-            *reinterpret_cast<f32x4 *>(dst + 8 * i) = lo4;
-            *reinterpret_cast<f32x4 *>(dst + 8 * i + 4) = hi4;
-        }
-    }
-    __syncthreads();
-
+    //      m = reference maximum of the raw scores, l = sum of exp, acc = un-normalised weighted values.
+    //      One round per tile of the wave; the exchange buffer is dead by now and the merge buffer takes its place.
     constexpr int EPL = D / 16;  // floats of a row per lane when 16 lanes share a row
     const int NP = kWaves / TR;  // parts to merge per row
     const int rr = lane >> 4, dc = lane & 15;
-    for (int ps = 0; ps < TR; ++ps) {
-        const int gr = 4 * TR * wave + 4 * ps + rr;  // row of the task: 16 * tile + n
-        const int tile = gr >> 4, n = gr & 15;
-        const int r = 16 * (tile0 + tile) + n;
-        if (tile >= ntiles || r >= R) continue;
-        float M = -INFINITY;
-        for (int s = 0; s < NP; ++s) M = fmaxf(M, mM[(tile + TR * s) * 16 + n]);
-        const float m_use = (M == -INFINITY) ? 0.f : M;
-        float L = 0.f;
-        float o[EPL];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) o[e] = 0.f;
-        for (int s = 0; s < NP; ++s) {
-            const int src = tile + TR * s;
-            const float w = __builtin_amdgcn_exp2f((mM[src * 16 + n] - m_use) * a.c);
-            L += w * mL[src * 16 + n];
-            const float *row = mO + (src * 16 + n) * OP + EPL * dc;
+    for (int u = 0; u < 2; ++u) {
+        if (u >= NTW) break;
+        const float l_tot = wave_row_sum(ts[u].rs.l);
+        __syncthreads();
+        if (g == 0) {
+            mM[wave * 16 + n16] = ts[u].rs.m;
+            mL[wave * 16 + n16] = l_tot;
+        }
+        if (D == 128 || g < 2) {
+            // this lane owns d in [32g, 32g+32) of row n16: d = 32g + 8i + c'
+            float *dst = mO + (wave * 16 + n16) * OP + 32 * g;
 #pragma unroll
-            for (int e = 0; e < EPL; e += 4) {
-                const f32x4 x = *reinterpret_cast<const f32x4 *>(row + e);
-                o[e] += w * x[0];
-                o[e + 1] += w * x[1];
-                o[e + 2] += w * x[2];
-                o[e + 3] += w * x[3];
+            for (int i = 0; i < 4; ++i) {
+                const f32x4 lo4 = {ts[u].o[0][i], ts[u].o[1][i], ts[u].o[2][i], ts[u].o[3][i]};
+                const f32x4 hi4 = {ts[u].o[4][i], ts[u].o[5][i], ts[u].o[6][i], ts[u].o[7][i]};
+                *reinterpret_cast<f32x4 *>(dst + 8 * i) = lo4;
+                *reinterpret_cast<f32x4 *>(dst + 8 * i + 4) = hi4;
             }
         }
-        const int pl = r / a.G, gh = r - pl * a.G;
-        const size_t ro = (size_t)(slot_base + pl) * a.Hq + (size_t)h * a.G + gh;
-        if (dc == 0) {
-            a.part_m[ro] = M;
-            a.part_l[ro] = L;
-        }
-        float *dst = a.part_acc + ro * D + EPL * dc;
+        __syncthreads();
+
+        for (int ps = 0; ps < TR; ++ps) {
+            const int gr = 4 * TR * wave + 4 * ps + rr;  // row among the tiles of this round: 16 * (wave % TR) + n
+            const int wt = gr >> 4, n = gr & 15;
+            const int tile = wt + 4 * u;
+            const int r = 16 * (tile0 + tile) + n;
+            if (tile >= ntiles || r >= R) continue;
+            float M = -INFINITY;
+            for (int sp = 0; sp < NP; ++sp) M = fmaxf(M, mM[(wt + TR * sp) * 16 + n]);
+            const float m_use = (M == -INFINITY) ? 0.f : M;
+            float L = 0.f;
+            float o[EPL];
 #pragma unroll
-        for (int e = 0; e < EPL; e += 4) *reinterpret_cast<f32x4 *>(dst + e) = f32x4{o[e], o[e + 1], o[e + 2], o[e + 3]};
+            for (int e = 0; e < EPL; ++e) o[e] = 0.f;
+            for (int sp = 0; sp < NP; ++sp) {
+                const int src = wt + TR * sp;
+                const float w = __builtin_amdgcn_exp2f((mM[src * 16 + n] - m_use) * a.c);
+                L += w * mL[src * 16 + n];
+                const float *row = mO + (src * 16 + n) * OP + EPL * dc;
+#pragma unroll
+                for (int e = 0; e < EPL; e += 4) {
+                    const f32x4 x = *reinterpret_cast<const f32x4 *>(row + e);
+                    o[e] += w * x[0];
+                    o[e + 1] += w * x[1];
+                    o[e + 2] += w * x[2];
+                    o[e + 3] += w * x[3];
+                }
+            }
+            const int pl = r / a.G, gh = r - pl * a.G;
+            const size_t ro = (size_t)(slot_base + pl) * a.Hq + (size_t)h * a.G + gh;
+            if (dc == 0) {
+                a.part_m[ro] = M;
+                a.part_l[ro] = L;
+            }
+            float *dst = a.part_acc + ro * D + EPL * dc;
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4)
+                *reinterpret_cast<f32x4 *>(dst + e) = f32x4{o[e], o[e + 1], o[e + 2], o[e + 3]};
+        }
     }
 #ifdef DEFT_TRACE
     if (a.trace && lane == 0) {

@@ -10,12 +10,12 @@
 
 namespace deft {
 
-// A stage-1 task is a (chunk, range of up to four 16-row tiles) pair; with the KV head taken from the
+// A stage-1 task is a (chunk, range of up to eight 16-row tiles) pair; with the KV head taken from the
 // workgroup id it is the job of one workgroup.  Its descriptor is kItemInts int32, read with scalar
 // loads, and carries everything the workgroup needs to start streaming a single-segment chunk
 // without touching any other table.
 constexpr int kItemInts = 16;
-constexpr int kMaxTilesPerTask = 4;
+constexpr int kMaxTilesPerTask = 8;
 enum ItemField {
     kItChunk = 0,     // chunk id
     kItTile0 = 1,     // first 16-row tile of the chunk's group handled by this task

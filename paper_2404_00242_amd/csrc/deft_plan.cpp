@@ -212,11 +212,11 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
     }
 }
 
-// Chunk size that fills an MI355X once.  Stage 1 runs one workgroup per (chunk, KV head, 64 rows of the
+// Chunk size that fills an MI355X once.  Stage 1 runs one workgroup per (chunk, KV head, 128 rows of the
 // chunk's group) and the chip holds two such workgroups on each of its 256 compute units; since a compute
 // unit streams at a fixed rate however many workgroups it holds, the kernel is fastest when every unit
 // gets the same number of bytes, i.e. when there are about 512 equal tasks.  The estimate weighs each
-// reached node's tokens by the number of 64-row tasks its own query group needs.
+// reached node's tokens by the number of 128-row tasks its own query group needs.
 extern "C" int32_t deft_suggest_chunk_size(const int32_t *node_tok_len, const int32_t *node_parent, int32_t n_nodes,
                                            const int32_t *query_node, int32_t nq, int32_t Hq, int32_t Hkv) {
     if (!node_tok_len || !node_parent || n_nodes < 1 || nq < 0 || (nq > 0 && !query_node)) return DEFT_EINVAL;
@@ -239,7 +239,7 @@ extern "C" int32_t deft_suggest_chunk_size(const int32_t *node_tok_len, const in
         long double task_tokens = 0;
         for (int32_t u = 0; u < n_nodes; ++u) {
             if (sub[u] == 0) continue;
-            const int64_t row_groups = (sub[u] * G + 63) / 64;
+            const int64_t row_groups = (sub[u] * G + 127) / 128;
             task_tokens += (long double)node_tok_len[u] * (long double)row_groups;
         }
         const long double per_task = task_tokens * Hkv / 512.0L;
@@ -299,7 +299,7 @@ extern "C" const char *deft_strerror(int status) {
 // ------------------------------------------------------------------------------------------------
 // Launch schedule.  The rows of a chunk's group, seen from one KV head, are (query of the group) x
 // (the G query heads that read this KV head): R = w * G rows, tiled 16 at a time (the N dimension
-// of the 16x16x32 MFMA).  A task covers up to four row tiles of one chunk and is run by a workgroup
+// of the 16x16x32 MFMA).  A task covers up to eight row tiles of one chunk and is run by a workgroup
 // of four waves; wider groups are cut into several tasks that re-read the chunk from L2.  The kernel
 // numbers its workgroups task * Hkv + kv_head, so the tasks that re-read one chunk for one head sit
 // Hkv workgroups apart; with Hkv a multiple of 8 and workgroups dealt round-robin to the 8 XCDs they
