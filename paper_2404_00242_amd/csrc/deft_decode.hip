@@ -60,13 +60,7 @@ struct Stage2Args {
     float c;
 };
 
-__device__ __forceinline__ u32x4 load16(const uint16_t *p) {
-#ifdef DEFT_NT_LOADS
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-#else
-    return *reinterpret_cast<const u32x4 *>(p);
-#endif
-}
+__device__ __forceinline__ u32x4 load16(const uint16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
 
 __device__ __forceinline__ float wave_row_max(float x) {
     // a row of a 16-row tile lives in lanes {n, n+16, n+32, n+48}
@@ -421,13 +415,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the block loops on scalar branches
     const int n16 = lane & 15;
     const int g = lane >> 4;
-#ifdef DEFT_HEAD_MAJOR
-    const int h = blockIdx.x / a.n_items;
-    const int item = blockIdx.x - h * a.n_items;
-#else
     const int item = blockIdx.x / a.Hkv;
     const int h = blockIdx.x - item * a.Hkv;
-#endif
     const int32_t *it = a.items + (size_t)item * deft::kItemInts;
     const int tile0 = it[deft::kItTile0], ntiles = it[deft::kItNTiles];
     const int seg0 = it[deft::kItSeg0], nseg = it[deft::kItNSeg];
