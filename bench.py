@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--chunk", type=int, default=0,
                     help="S_t, tokens per chunk (0 = deft_suggest_chunk_size for this tree; 128 = the paper's default)")
+    ap.add_argument("--mode", default="flatten", choices=["flatten", "node", "node_chunk", "query"],
+                    help="partitioning strategy of the plan (flatten = the paper's method and the headline; the others "
+                         "are its ablation / comparison strategies run on the same kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a few plain 1 GiB device-to-device copies (known size) so that a rocprofv3 "
@@ -111,7 +114,8 @@ def main():
         args.chunk = binding.deft_suggest_chunk_size(nl, par, qn, Hq, Hkv)
 
     # sizes are a property of the tree: allocate the image buffer and the workspace once
-    probe = binding.deft_plan(nb, nl, par, qn, tree.ntok, args.chunk)
+    mode_flag = binding.SPLIT_MODES[args.mode]
+    probe = binding.deft_plan(nb, nl, par, qn, tree.ntok, args.chunk, mode_flag)
     view = probe.view()
     img_bytes = probe.device_bytes(Hq, Hkv)
     ws_bytes = probe.workspace_bytes(Hq, Hkv, d)
@@ -132,7 +136,8 @@ def main():
         h = vp()
         if lib.deft_suggest_chunk_size(nlp, parp, tree.n_nodes, qnp, tree.nq, Hq, Hkv) < 0:
             raise RuntimeError("deft_suggest_chunk_size failed")
-        check(lib.deft_plan(nbp, nlp, parp, tree.n_nodes, qnp, tree.nq, tree.ntok, args.chunk, 0, ctypes.byref(h)),
+        check(lib.deft_plan(nbp, nlp, parp, tree.n_nodes, qnp, tree.nq, tree.ntok, args.chunk, mode_flag,
+                            ctypes.byref(h)),
               "deft_plan")
         if lib.deft_plan_device_bytes(h, Hq, Hkv) > img_bytes:
             raise RuntimeError("plan image grew")
@@ -187,7 +192,10 @@ def main():
     s1_us = float(np.mean(s1_ms)) * 1e3
     s2_us = float(np.mean(s2_ms)) * 1e3
 
-    kv_bytes = view["n_flat"] * Hkv * 2 * d * 2  # K and V of every reached token, once per KV head
+    # K and V of every reached token, once per KV head: what the method itself must move (a Q-guided plan
+    # moves more, but the useful bytes stay these)
+    n_reached = int(sum(int(nl[u]) for u in set(int(x) for x in view["seg_node"])))
+    kv_bytes = n_reached * Hkv * 2 * d * 2
     achieved = kv_bytes / (s1_us * 1e-6) / 1e9
     workload = tree.name
 
@@ -205,7 +213,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": workload, "Hq": Hq, "Hkv": Hkv, "d": d, "ntok": tree.ntok, "nq": tree.nq,
+            "workload": workload, "split": args.mode, "Hq": Hq, "Hkv": Hkv, "d": d, "ntok": tree.ntok, "nq": tree.nq,
             "layers_per_step": L, "chunk_size": view["chunk_size"], "n_chunks": view["n_chunks"],
             "n_slots": view["n_slots"], "path_tokens": workloads.path_token_count(tree),
         },
@@ -218,7 +226,7 @@ def main():
             "kernel": "deft_stage1 (partial attention, one layer-call)",
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": kv_bytes,
-            "traffic": traffic_from_profiles(workload),
+            "traffic": traffic_from_profiles(workload) if args.mode == "flatten" else None,
         },
     }
 

@@ -40,6 +40,23 @@ typedef enum deft_status {
 #define DEFT_OUT_BF16 0u
 #define DEFT_OUT_F32 1u
 
+/*
+ * How deft_plan partitions the tree's KV and groups it with queries (flags argument).  The paper's
+ * method is DEFT_SPLIT_FLATTEN; the others are the strategies it is compared with (Table 2, the
+ * split-strategy ablation of Table 6 and the IO comparison of Table 17), expressed in the same plan
+ * encoding so that the same kernels run them.
+ *   DEFT_SPLIT_FLATTEN     KV-guided; depth-first flatten, a cut every chunk_size tokens (Remark 3.1)
+ *   DEFT_SPLIT_NODE        KV-guided; one group per tree node, chunk_size ignored (DeFT-Node, Algorithm 1)
+ *   DEFT_SPLIT_NODE_CHUNK  KV-guided; every node cut into blocks of chunk_size tokens on its own
+ *   DEFT_GROUP_QUERY       Q-guided; every query grouped with its own root-to-node KV, cut into blocks
+ *                          of chunk_size tokens (the Flash-Decoding split): shared prefixes are read
+ *                          once per query instead of once
+ */
+#define DEFT_SPLIT_FLATTEN 0u
+#define DEFT_SPLIT_NODE 1u
+#define DEFT_SPLIT_NODE_CHUNK 2u
+#define DEFT_GROUP_QUERY 3u
+
 #define DEFT_DEFAULT_CHUNK 128 /* the paper's default KV block size (chunk-size ablation, Fig. 11) */
 #define DEFT_MAX_CHUNK 4096
 
@@ -104,13 +121,13 @@ typedef struct deft_plan_view {
  *     may share a node and may sit on inner nodes.
  * chunk_size : S_t, tokens per chunk; 0 selects DEFT_DEFAULT_CHUNK; otherwise a positive
  *     multiple of 32, at most DEFT_MAX_CHUNK.
- * flags      : reserved, must be 0.
+ * flags      : DEFT_SPLIT_FLATTEN (0, the paper's method) or one of the comparison strategies above.
  * out_plan   : receives a host object owned by the library; release with deft_plan_destroy.
  *     The plan is immutable, depends on the tree only, and can be reused for every layer
  *     and every call that sees the same tree.
  * Errors: DEFT_EINVAL for any malformed input (null pointer, n_nodes < 1, nq < 0, parent out
  *     of range or cyclic, range outside the cache or overlapping, query node out of range,
- *     bad chunk_size); DEFT_ENOMEM.  *out_plan is NULL on error.
+ *     bad chunk_size, unknown flags); DEFT_ENOMEM.  *out_plan is NULL on error.
  */
 int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_len, const int32_t *node_parent,
               int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size,

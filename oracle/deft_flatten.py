@@ -115,6 +115,8 @@ def attention_by_plan(plan, Q, K, V, scale=None):
     O = np.zeros((nq, Hq, d))
     for p in range(nq):
         slots = plan["q_part_slot"][int(plan["q_part_ptr"][p]):int(plan["q_part_ptr"][p + 1])]
+        if len(slots) == 0:
+            continue  # a query no chunk is grouped with (its path holds no token): zeros
         for h in range(Hq):
             O[q_order[p], h] = seg_attn([part_o[s, h] for s in slots], [part_lse[s, h] for s in slots])
     return O

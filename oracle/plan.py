@@ -17,6 +17,12 @@ following readings are used (each is also listed in the design notes):
     ceil(w/64) little-endian 64-bit words per segment;
   * a query attends to its own node's tokens (paths are inclusive).
 
+Besides DeFT-Flatten (mode "flatten") the same encoding expresses the paper's
+other partitioning strategies (Table 2): DeFT-Node ("node", Algorithm 1: one
+group per tree node), DeFT-Node-Chunk ("node_chunk": nodes cut into blocks) and
+Q-guided grouping with the Flash-Decoding split ("query": each query with its own
+path, shared prefixes repeated), which the ablations and the IO comparison need.
+
 Everything is integer work; the output arrays are the canonical encoding that
 the C++ planner must reproduce bit for bit.
 """
@@ -61,7 +67,7 @@ def _validate(nb, nl, par, qn, ntok, chunk_size):
             raise PlanError("query node out of range")
 
 
-def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, chunk_size=128):
+def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, chunk_size=128, mode="flatten"):
     nb = [int(x) for x in node_tok_begin]
     nl = [int(x) for x in node_tok_len]
     par = [int(x) for x in node_parent]
@@ -110,30 +116,70 @@ def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, ch
 
     # 4. flattened sequence: reached, non-empty nodes in preorder
     flat_nodes = [u for u in pre if q_hi[u] > q_lo[u] and nl[u] > 0]
-    n_flat = sum(nl[u] for u in flat_nodes)
 
-    # 5./6. even chunks and the node pieces (segments) inside them
-    m = (n_flat + B - 1) // B
+    # 5./6. the split: chunks as lists of node pieces (physical begin, length, query interval, node)
+    chunks = []
+    if mode == "flatten":
+        # DeFT-Flatten (Remark 3.1): cut the flattened sequence every B tokens, whatever node the cut falls in
+        cur, room = [], B
+        for u in flat_nodes:
+            off = 0
+            while off < nl[u]:
+                if room == 0:
+                    chunks.append(cur)
+                    cur, room = [], B
+                take = min(room, nl[u] - off)
+                cur.append((nb[u] + off, take, q_lo[u], q_hi[u], u))
+                off += take
+                room -= take
+        if cur:
+            chunks.append(cur)
+    elif mode == "node":
+        # DeFT-Node (Algorithm 1): one QKV group per tree node, however long
+        for u in flat_nodes:
+            chunks.append([(nb[u], nl[u], q_lo[u], q_hi[u], u)])
+    elif mode == "node_chunk":
+        # DeFT-Node-Chunk (Section 3.3): node-wise grouping, each node cut into blocks of B tokens
+        for u in flat_nodes:
+            for off in range(0, nl[u], B):
+                chunks.append([(nb[u] + off, min(B, nl[u] - off), q_lo[u], q_hi[u], u)])
+    elif mode == "query":
+        # Q-guided grouping with the Flash-Decoding split (Section 3.1; Table 2): every query is grouped with
+        # its own root-to-node KV, cut into blocks of B tokens; shared prefixes are repeated per query
+        for pos in range(nq):
+            path = []
+            u = qn[q_order[pos]]
+            while u != -1:
+                path.append(u)
+                u = par[u]
+            cur, room = [], B
+            for u in reversed(path):
+                off = 0
+                while off < nl[u]:
+                    if room == 0:
+                        chunks.append(cur)
+                        cur, room = [], B
+                    take = min(room, nl[u] - off)
+                    cur.append((nb[u] + off, take, pos, pos + 1, u))
+                    off += take
+                    room -= take
+            if cur:
+                chunks.append(cur)
+    else:
+        raise PlanError("unknown split mode")
+
+    m = len(chunks)
+    n_flat = sum(piece[1] for ch in chunks for piece in ch)
     chunk_seg_ptr = [0]
     seg_tok_begin, seg_len, seg_qlo, seg_qhi, seg_node = [], [], [], [], []
-    room = B if m > 0 else 0
-    for u in flat_nodes:
-        off = 0
-        while off < nl[u]:
-            if room == 0:
-                chunk_seg_ptr.append(len(seg_len))
-                room = B
-            take = min(room, nl[u] - off)
-            seg_tok_begin.append(nb[u] + off)
-            seg_len.append(take)
-            seg_qlo.append(q_lo[u])
-            seg_qhi.append(q_hi[u])
+    for ch in chunks:
+        for (b, ln, lo, hi, u) in ch:
+            seg_tok_begin.append(b)
+            seg_len.append(ln)
+            seg_qlo.append(lo)
+            seg_qhi.append(hi)
             seg_node.append(u)
-            off += take
-            room -= take
-    if m > 0:
         chunk_seg_ptr.append(len(seg_len))
-    assert len(chunk_seg_ptr) == m + 1 or (m == 0 and chunk_seg_ptr == [0])
     nseg = len(seg_len)
 
     # 7. KV-guided grouping: the chunk's query interval and its partial-result slots
@@ -176,7 +222,7 @@ def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, ch
         "chunk_size": B, "n_nodes": n, "nq": nq, "n_flat": n_flat,
         "n_chunks": m, "n_segs": nseg, "n_slots": n_slots,
         "q_order": i32(q_order), "node_q_lo": i32(q_lo), "node_q_hi": i32(q_hi),
-        "chunk_seg_ptr": i32(chunk_seg_ptr if m > 0 else [0]),
+        "chunk_seg_ptr": i32(chunk_seg_ptr),
         "seg_tok_begin": i32(seg_tok_begin), "seg_len": i32(seg_len),
         "seg_qlo": i32(seg_qlo), "seg_qhi": i32(seg_qhi), "seg_node": i32(seg_node),
         "chunk_qlo": i32(chunk_qlo), "chunk_qhi": i32(chunk_qhi), "chunk_slot_base": i32(chunk_slot_base),

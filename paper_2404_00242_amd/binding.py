@@ -19,6 +19,13 @@ LIB_PATH = os.environ.get("DEFT_LIB") or os.path.join(_PKG, "libdeft.so")
 
 DEFT_OUT_BF16 = 0
 DEFT_OUT_F32 = 1
+# deft_plan flags: how the tree's KV is partitioned and grouped with queries
+DEFT_SPLIT_FLATTEN = 0
+DEFT_SPLIT_NODE = 1
+DEFT_SPLIT_NODE_CHUNK = 2
+DEFT_GROUP_QUERY = 3
+SPLIT_MODES = {"flatten": DEFT_SPLIT_FLATTEN, "node": DEFT_SPLIT_NODE, "node_chunk": DEFT_SPLIT_NODE_CHUNK,
+               "query": DEFT_GROUP_QUERY}
 
 EXPORTS = (
     "deft_plan", "deft_suggest_chunk_size", "deft_plan_view", "deft_plan_device_bytes", "deft_plan_upload", "deft_workspace_bytes",

@@ -45,7 +45,8 @@ struct Stage1Args {
     const int32_t *seg_tok_begin, *seg_len, *seg_qlo, *seg_qhi, *seg_off;
     const int32_t *q_order;
     const int32_t *items;  // deft::kItemInts int32 per work item, see deft_internal.h
-    int32_t n_items, Hq, Hkv, G, chunk_size;
+    int32_t n_items, Hq, Hkv, G;
+    int32_t table_len;  // entries of the LDS per-token table: longest multi-piece chunk, in whole blocks
     float c;  // scale * log2(e): probabilities are 2^((s - m) * c)
 #ifdef DEFT_TRACE
     unsigned long long *trace;  // developer build only: 4 timestamps per wave
@@ -404,8 +405,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     float *mM = mO + kWaves * 16 * OP;
     float *mL = mM + kWaves * 16;
     int32_t *s_row = reinterpret_cast<int32_t *>(s_raw + kXbufBytes);   // per-token table
-    int32_t *s_qlo = s_row + a.chunk_size;
-    int32_t *s_qhi = s_qlo + a.chunk_size;
+    int32_t *s_qlo = s_row + a.table_len;
+    int32_t *s_qhi = s_qlo + a.table_len;
 
 #ifdef DEFT_TRACE
     const unsigned long long t_begin = wall_clock64();
@@ -707,7 +708,7 @@ bool launch_stage1(const deft::Schedule &S, Stage1Args a1, const uint8_t *image,
     a1.items = reinterpret_cast<const int32_t *>(image + S.off_items);
     a1.n_items = S.n_items;
     if (a1.n_items == 0) return true;
-    const size_t lds = kXbufBytes + 3 * (size_t)a1.chunk_size * sizeof(int32_t);
+    const size_t lds = kXbufBytes + 3 * (size_t)a1.table_len * sizeof(int32_t);
     // the kernel may use more than the default 64 KB of dynamic LDS: raise the limit once per device
     static std::atomic<uint64_t> configured[2];  // bit i set: done on device i, per head dimension
     int dev = 0;
@@ -787,7 +788,7 @@ int run_stage1(const deft_plan_t *plan, const Call &call, const void *q, const v
     a1.Hq = Hq;
     a1.Hkv = Hkv;
     a1.G = Hq / Hkv;
-    a1.chunk_size = plan->chunk_size;
+    a1.table_len = S.table_len;
     a1.c = call.c;
 #ifdef DEFT_TRACE
     {

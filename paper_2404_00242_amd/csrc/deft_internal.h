@@ -41,6 +41,7 @@ struct Schedule {
     size_t off_q_part_ptr = 0, off_q_part_slot = 0;
     size_t off_items = 0;     // task descriptors
     int32_t n_items = 0;
+    int32_t table_len = 32;   // longest chunk made of several pieces, rounded up to whole blocks: LDS table size
     std::vector<uint8_t> host_image;  // packed image, kept for repeated uploads
 };
 
@@ -48,6 +49,7 @@ struct Schedule {
 
 struct deft_plan_s {
     int32_t chunk_size = 0, n_nodes = 0, nq = 0, ntok = 0, n_flat = 0;
+    uint32_t mode = 0;  // DEFT_SPLIT_* / DEFT_GROUP_QUERY
     std::vector<int32_t> q_order, node_q_lo, node_q_hi;
     std::vector<int32_t> chunk_seg_ptr, seg_tok_begin, seg_len, seg_qlo, seg_qhi, seg_node;
     std::vector<int32_t> chunk_qlo, chunk_qhi, chunk_slot_base;

@@ -58,7 +58,8 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
                          uint32_t flags, deft_plan_t **out_plan) {
     if (out_plan) *out_plan = nullptr;
     if (!out_plan || !node_tok_begin || !node_tok_len || !node_parent) return DEFT_EINVAL;
-    if (n_nodes < 1 || nq < 0 || ntok < 0 || flags != 0) return DEFT_EINVAL;
+    if (n_nodes < 1 || nq < 0 || ntok < 0 || flags > DEFT_GROUP_QUERY) return DEFT_EINVAL;
+    const uint32_t mode = flags;
     if (nq > 0 && !query_node) return DEFT_EINVAL;
     if (chunk_size == 0) chunk_size = DEFT_DEFAULT_CHUNK;
     if (chunk_size < 0 || chunk_size % 32 != 0 || chunk_size > DEFT_MAX_CHUNK) return DEFT_EINVAL;
@@ -89,6 +90,7 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
         P->n_nodes = n;
         P->nq = nq;
         P->ntok = ntok;
+        P->mode = mode;
 
         // ---- depth-first renumbering of the queries ------------------------------------------
         // A node's own queries come first, then its subtrees, so the queries whose path contains u
@@ -121,31 +123,95 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
             for (int32_t j = 0; j < nq; ++j) P->q_order[cursor[query_node[j]]++] = j;
         }
 
-        // ---- flatten + even block-wise split -------------------------------------------------
+        // ---- the split: chunks as runs of node pieces ---------------------------------------------
         const int32_t S = chunk_size;
         int64_t flat = 0;
-        int32_t room = 0;  // tokens still free in the open chunk
-        for (int32_t i = 0; i < n; ++i) {
-            int32_t u = pre[i];
-            if (P->node_q_hi[u] == P->node_q_lo[u] || node_tok_len[u] == 0) continue;
-            int32_t done = 0, len = node_tok_len[u];
-            while (done < len) {
-                if (room == 0) {
-                    P->chunk_seg_ptr.push_back(P->n_segs());
-                    room = S;
-                }
-                int32_t take = std::min(room, len - done);
-                P->seg_tok_begin.push_back(node_tok_begin[u] + done);
-                P->seg_len.push_back(take);
-                P->seg_qlo.push_back(P->node_q_lo[u]);
-                P->seg_qhi.push_back(P->node_q_hi[u]);
-                P->seg_node.push_back(u);
-                done += take;
-                room -= take;
+        bool open = false;
+        auto piece = [&](int32_t begin, int32_t len, int32_t lo, int32_t hi, int32_t node) {
+            if (!open) {
+                P->chunk_seg_ptr.push_back(P->n_segs());
+                open = true;
             }
+            P->seg_tok_begin.push_back(begin);
+            P->seg_len.push_back(len);
+            P->seg_qlo.push_back(lo);
+            P->seg_qhi.push_back(hi);
+            P->seg_node.push_back(node);
             flat += len;
+        };
+        auto close = [&]() { open = false; };
+        auto reached = [&](int32_t u) { return P->node_q_hi[u] > P->node_q_lo[u] && node_tok_len[u] > 0; };
+        switch (mode) {
+            case DEFT_SPLIT_FLATTEN: {
+                // Flattened Tree KV Splitting (Remark 3.1): depth-first order, a cut every S tokens
+                int32_t room = S;
+                for (int32_t i = 0; i < n; ++i) {
+                    const int32_t u = pre[i];
+                    if (!reached(u)) continue;
+                    int32_t done = 0;
+                    const int32_t len = node_tok_len[u];
+                    while (done < len) {
+                        if (room == 0) {
+                            close();
+                            room = S;
+                        }
+                        const int32_t take = std::min(room, len - done);
+                        piece(node_tok_begin[u] + done, take, P->node_q_lo[u], P->node_q_hi[u], u);
+                        done += take;
+                        room -= take;
+                    }
+                }
+                break;
+            }
+            case DEFT_SPLIT_NODE:
+                // DeFT-Node (Algorithm 1): one group per tree node, whatever its length
+                for (int32_t i = 0; i < n; ++i) {
+                    const int32_t u = pre[i];
+                    if (!reached(u)) continue;
+                    piece(node_tok_begin[u], node_tok_len[u], P->node_q_lo[u], P->node_q_hi[u], u);
+                    close();
+                }
+                break;
+            case DEFT_SPLIT_NODE_CHUNK:
+                // DeFT-Node-Chunk: node-wise groups, every node cut into blocks of S tokens on its own
+                for (int32_t i = 0; i < n; ++i) {
+                    const int32_t u = pre[i];
+                    if (!reached(u)) continue;
+                    for (int32_t done = 0; done < node_tok_len[u]; done += S) {
+                        piece(node_tok_begin[u] + done, std::min(S, node_tok_len[u] - done), P->node_q_lo[u],
+                              P->node_q_hi[u], u);
+                        close();
+                    }
+                }
+                break;
+            case DEFT_GROUP_QUERY: {
+                // Q-guided grouping with the Flash-Decoding split: each query with its own root-to-node KV
+                std::vector<int32_t> path;
+                for (int32_t pos = 0; pos < nq; ++pos) {
+                    path.clear();
+                    for (int32_t u = query_node[P->q_order[pos]]; u != -1; u = node_parent[u]) path.push_back(u);
+                    int32_t room = S;
+                    for (auto it = path.rbegin(); it != path.rend(); ++it) {
+                        const int32_t u = *it, len = node_tok_len[u];
+                        int32_t done = 0;
+                        while (done < len) {
+                            if (room == 0) {
+                                close();
+                                room = S;
+                            }
+                            const int32_t take = std::min(room, len - done);
+                            piece(node_tok_begin[u] + done, take, pos, pos + 1, u);
+                            done += take;
+                            room -= take;
+                        }
+                    }
+                    close();
+                }
+                break;
+            }
+            default: return DEFT_EINVAL;
         }
-        if (flat > INT32_MAX) return DEFT_EINVAL;
+        if (flat > INT32_MAX || P->seg_len.size() > (size_t)INT32_MAX / 2) return DEFT_EINVAL;
         P->n_flat = (int32_t)flat;
         P->chunk_seg_ptr.push_back(P->n_segs());  // closes the last chunk; {0} when there is none
         const int32_t m = (int32_t)P->chunk_seg_ptr.size() - 1;
@@ -311,6 +377,7 @@ static size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
 static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
     S.group = G;
+    S.table_len = 32;
     const int32_t m = P->n_chunks();
     std::vector<int32_t> items;
     std::vector<int32_t> seg_off(P->n_segs(), 0);
@@ -321,6 +388,7 @@ static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
             seg_off[s] = len;
             len += P->seg_len[s];
         }
+        if (s1 - s0 > 1) S.table_len = std::max(S.table_len, (len + 31) / 32 * 32);
         const int32_t width = P->chunk_qhi[c] - P->chunk_qlo[c];
         const int64_t rows = (int64_t)width * G;
         const int32_t tiles = (int32_t)((rows + 15) / 16);

@@ -20,9 +20,10 @@ pytestmark = pytest.mark.gpu
 ABS_TOL, REL_TOL = 2e-3, 1e-2
 
 
-def run_gpu(t, Q, K, V, chunk_size=0, out_dtype=torch.bfloat16, scale=0.0):
+def run_gpu(t, Q, K, V, chunk_size=0, out_dtype=torch.bfloat16, scale=0.0, mode="flatten"):
     dev = torch.device("cuda:0")
-    plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, chunk_size)
+    plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, chunk_size,
+                             binding.SPLIT_MODES[mode])
     q, k, v = Q.to(dev), K.to(dev), V.to(dev)
     o = binding.deft_tree_attn_decode(plan, q, k, v, out_dtype=out_dtype, scale=scale)
     torch.cuda.synchronize()
@@ -117,6 +118,23 @@ def test_stage1_partials_match_algorithm4_and_stage2_completes_them():
     assert rc == 0
     torch.cuda.synchronize()
     check(o.cpu().numpy().astype(np.float64), reference(t, Q, K, V), strict=False)
+
+
+@pytest.mark.parametrize("mode", ["node", "node_chunk", "query"])
+def test_other_partitioning_strategies_give_the_same_attention(mode):
+    # DeFT-Node, DeFT-Node-Chunk and Q-guided grouping run on the same kernels through the plan
+    for cfg in (1, 2, 3):
+        t = wl.make_config(cfg)
+        print(f"\n  config {cfg} mode {mode}", flush=True)
+        Q, K, V = wl.make_qkv(t)
+        got, _ = run_gpu(t, Q, K, V, chunk_size=128, mode=mode)
+        check(got, reference(t, Q, K, V), strict=True)
+    for seed in range(6):
+        t = wl.random_tree(500 + seed, n_nodes=3 + 2 * seed, max_len=150, nq=3 + 4 * seed, Hq=8, Hkv=2, d=128,
+                           n_roots=1 + seed % 2)
+        Q, K, V = wl.make_qkv(t)
+        got, _ = run_gpu(t, Q, K, V, chunk_size=64, out_dtype=torch.float32, mode=mode)
+        check(got, reference(t, Q, K, V), strict=False)
 
 
 def test_tiny_variant_with_320_tokens():

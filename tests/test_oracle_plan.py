@@ -25,8 +25,8 @@ from paper_2404_00242_amd import workloads as wl
 GOLDEN = sorted(glob.glob(os.path.join(os.path.dirname(__file__), "golden", "plan_*.json")))
 
 
-def plan_of(t, B=128):
-    return flatten_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B)
+def plan_of(t, B=128, mode="flatten"):
+    return flatten_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B, mode)
 
 
 def path_pairs(t):
@@ -59,12 +59,16 @@ def plan_pairs(p, use_bits):
     return c
 
 
-def check_invariants(t, p, B):
+def check_invariants(t, p, B, mode="flatten"):
     m = p["n_chunks"]
-    assert m == -(-p["n_flat"] // B)                                  # m = ceil(n_T / S_t)
+    if mode == "flatten":
+        assert m == -(-p["n_flat"] // B)                                  # m = ceil(n_T / S_t)
     for ch in range(m):
         n = int(p["seg_len"][p["chunk_seg_ptr"][ch]:p["chunk_seg_ptr"][ch + 1]].sum())
-        assert n == (B if ch < m - 1 else p["n_flat"] - B * (m - 1))  # even blocks, short tail
+        if mode == "flatten":
+            assert n == (B if ch < m - 1 else p["n_flat"] - B * (m - 1))  # even blocks, short tail
+        elif mode != "node":
+            assert 0 < n <= B
         assert p["chunk_seg_ptr"][ch + 1] > p["chunk_seg_ptr"][ch]
     # parent's query interval contains the child's
     for u in range(t.n_nodes):
@@ -185,3 +189,36 @@ def test_degenerate_plans():
     # a query whose path has no tokens
     p = flatten_plan([0, 0], [0, 0], [-1, 0], [1], 0, 32)
     assert p["n_chunks"] == 0 and p["q_part_ptr"].tolist() == [0, 0]
+
+
+@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("mode", ["node", "node_chunk", "query"])
+def test_other_partitioning_strategies_cover_the_same_pairs(seed, mode):
+    # DeFT-Node, DeFT-Node-Chunk and Q-guided grouping (Table 2) in the same encoding: every strategy must
+    # enumerate every (query, path token) pair exactly once, and Algorithm 4 on it must give the definition
+    t = wl.random_tree(300 + seed, n_nodes=3 + seed, max_len=50, nq=2 + seed, Hq=2, Hkv=1, d=8, n_roots=1 + seed % 2)
+    B = 32
+    p = plan_of(t, B, mode)
+    check_invariants(t, p, B, mode)
+    reached = [u for u in range(t.n_nodes) if p["node_q_hi"][u] > p["node_q_lo"][u] and t.node_tok_len[u] > 0]
+    if mode == "node":
+        assert p["n_chunks"] == len(reached) == p["n_segs"]                       # k = #node
+    if mode == "node_chunk":
+        assert p["n_chunks"] == sum(-(-int(t.node_tok_len[u]) // B) for u in reached)  # k = sum ceil(n_i / b_s)
+    if mode == "query":
+        assert p["n_flat"] == wl.path_token_count(t)                              # KV IO = 2 d sum N_i
+        assert np.all(p["chunk_qhi"] - p["chunk_qlo"] == 1)
+    if mode != "query":
+        assert p["n_flat"] == sum(int(t.node_tok_len[u]) for u in reached)        # KV IO = 2 d N_tree
+    if seed < 4:
+        Q, K, V = (x.float().numpy() for x in wl.make_qkv(t))
+        ref = oracle.tree_attention(Q, K, V, t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node)
+        np.testing.assert_allclose(deft_flatten.attention_by_plan(p, Q, K, V), ref, rtol=0, atol=1e-12)
+
+
+def test_share_factor_of_the_few_shot_tree():
+    # F_s = sum N_i / N_tree (Appendix A.5): the Q-guided plan reads F_s times the tokens of the KV-guided one
+    t = wl.make_config(2)
+    kv, qg = plan_of(t, 128, "flatten"), plan_of(t, 128, "query")
+    assert kv["n_flat"] == 9120 and qg["n_flat"] == 85120
+    assert abs(qg["n_flat"] / kv["n_flat"] - 9.333) < 1e-3

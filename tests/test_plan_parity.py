@@ -17,9 +17,10 @@ ARRAYS = ("q_order", "node_q_lo", "node_q_hi", "chunk_seg_ptr", "seg_tok_begin",
 SCALARS = ("chunk_size", "n_nodes", "nq", "n_flat", "n_chunks", "n_segs", "n_slots")
 
 
-def assert_same_plan(t, B):
-    ref = flatten_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B)
-    got = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B).view()
+def assert_same_plan(t, B, mode="flatten"):
+    ref = flatten_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B, mode)
+    got = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B,
+                            binding.SPLIT_MODES[mode]).view()
     for s in SCALARS:
         assert got[s] == ref[s], s
     assert got["n_mask_words"] == len(ref["seg_mask"])
@@ -139,3 +140,16 @@ def test_suggested_chunk_size():
         binding.deft_suggest_chunk_size([4, 4], [-1, 0], [1], 4, 3)     # Hq % Hkv != 0
     with pytest.raises(binding.DeftError):
         binding.deft_suggest_chunk_size([4, 4], [-1, 0], [7], 4, 2)     # query node out of range
+
+
+@pytest.mark.parametrize("mode", ["node", "node_chunk", "query"])
+def test_other_partitioning_strategies(mode):
+    for seed in range(30):
+        t = wl.random_tree(400 + seed, n_nodes=1 + seed % 17, max_len=120, nq=(seed * 3) % 19, n_roots=1 + seed % 3,
+                           zero_len_prob=0.15)
+        for B in (32, 128):
+            assert_same_plan(t, B, mode)
+    for cfg in (1, 2, 3):
+        assert_same_plan(wl.make_config(cfg), 128, mode)
+    with pytest.raises(binding.DeftError):
+        binding.deft_plan([0], [4], [-1], [0], 4, 32, 7)       # unknown strategy
