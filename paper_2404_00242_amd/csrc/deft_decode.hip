@@ -69,11 +69,6 @@ __device__ __forceinline__ float wave_row_max(float x) {
     x = fmaxf(x, __shfl_xor(x, 32));
     return x;
 }
-__device__ __forceinline__ float wave_row_sum(float x) {
-    x += __shfl_xor(x, 16);
-    x += __shfl_xor(x, 32);
-    return x;
-}
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -134,13 +129,17 @@ __device__ __forceinline__ void load_block(KVRegs<D> &r, const ChunkCtx &c, int 
 // Running softmax state of one row (held redundantly by the row's four lanes).
 //   m  : reference maximum of the raw scores, -inf while the row has seen no visible token
 //   mc : (m, or 0 while m is -inf) * cs, the value subtracted inside the exponential
-//   l  : this lane's share of sum exp2(s * cs - mc)
+//   l  : sum over all tokens so far of the bf16-rounded exp2(s * cs - mc), i.e. of exactly the weights
+//        that enter the P.V product.  It is accumulated by one more MFMA per block whose A operand is all
+//        ones (every row of that product is the column sum of P^T), which costs the idle matrix pipe 16
+//        cycles instead of 8 VALU adds and leaves the total in every lane of the row.
 // The reference is only raised when some score exceeds it by more than kLazyLog2 / cs (probabilities may
 // then reach 2^kLazyLog2, harmless in bf16 and fp32); otherwise a block costs no cross-lane traffic and
 // no rescaling of the accumulators.  Any reference gives the same (m, l, acc) up to rounding, because the
 // merge of eq. 1 only needs the three to be consistent.
 struct RowState {
-    float m, mc, l;
+    float m, mc;
+    f32x4 l;  // four identical copies (rows 4g..4g+3 of the all-ones product)
 };
 constexpr float kLazyLog2 = 8.0f;
 
@@ -222,19 +221,22 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
             for (int cc = 0; cc < 8; ++cc) ts[t].o[cc] *= alpha;
         }
         float pv[8];
-        float psum = 0.f;
 #pragma unroll
         for (int aa = 0; aa < 2; ++aa)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float e = __builtin_amdgcn_exp2f(fmaf(sacc[t][aa][i], cs, -st.mc));
-                pv[4 * aa + i] = e;
-                psum += e;
-            }
-        st.l += psum;
+            for (int i = 0; i < 4; ++i) pv[4 * aa + i] = __builtin_amdgcn_exp2f(fmaf(sacc[t][aa][i], cs, -st.mc));
         const u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]),
                           pack_bf16(pv[6], pv[7])};
         preg[t] = __builtin_bit_cast(bf16x8, pk);
+    }
+
+    // l += column sums of P^T
+    {
+        const u32x4 one4 = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // eight bf16 1.0
+        const bf16x8 ones = __builtin_bit_cast(bf16x8, one4);
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            ts[t].rs.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, preg[t], ts[t].rs.l, 0, 0, 0);
     }
 
     // O^T += V^T P^T.  The V^T operand of product c' = 2*c2 + {0,1} is a 16-bit interleave of token pairs:
@@ -496,7 +498,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
         ts[u].qpos = ok ? cqlo + pl : -1;
         q_user[u] = 0;
         if (ok) q_user[u] = a.q_order[cqlo + pl];
-        ts[u].rs = RowState{-INFINITY, 0.f, 0.f};
+        ts[u].rs = RowState{-INFINITY, 0.f, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc) ts[u].o[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
@@ -552,7 +554,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
         if (u >= NTW) break;
-        const float l_tot = wave_row_sum(ts[u].rs.l);
+        const float l_tot = ts[u].rs.l[0];
         __syncthreads();
         if (g == 0) {
             mM[wave * 16 + n16] = ts[u].rs.m;
