@@ -134,6 +134,25 @@ int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_len, const 
               uint32_t flags, deft_plan_t **out_plan);
 
 /*
+ * The same preparation phase for a paged KV cache (the storage the paper's headline results use,
+ * Section 4.2: tokens of a node are scattered over fixed-size pages of one pool and nothing is
+ * materialised).  K and V are then bf16 [n_pool_pages * page_size, Hkv, d]; token t of node u is row
+ * page_ids[node_page_ptr[u] + t / page_size] * page_size + t % page_size.  page_size = 1 is a
+ * token-level pool.
+ *
+ * node_page_ptr : host int32[n_nodes+1], node_page_ptr[0] = 0; node u owns page_ids[node_page_ptr[u] ..
+ *                 node_page_ptr[u+1]) and needs at least ceil(node_tok_len[u] / page_size) of them
+ *                 (further ones are ignored).  A page may belong to one node only.
+ * The plan is the one deft_plan would give for the same tree, except that segments are also cut
+ * where a node's storage is not contiguous (consecutive pool pages are joined into one run first).
+ * Everything else, including errors, is as for deft_plan; the decode calls are the same.
+ */
+int deft_plan_paged(const int32_t *node_page_ptr, const int32_t *page_ids, int32_t page_size, int32_t n_pool_pages,
+                    const int32_t *node_tok_len, const int32_t *node_parent, int32_t n_nodes,
+                    const int32_t *query_node, int32_t nq, int32_t chunk_size, uint32_t flags,
+                    deft_plan_t **out_plan);
+
+/*
  * A chunk size S_t suited to this tree on an MI355X (the paper leaves S_t as a tuning knob, Fig. 11):
  * the multiple of 128 in [128, 1024] that makes the number of stage-1 tasks, (chunk, KV head, 128 rows of
  * the chunk's query group), about twice the number of compute units, so that every unit streams the

@@ -48,6 +48,12 @@ def _lib():
             i32p, i32p, i32p, ctypes.c_int32, i32p, ctypes.c_int32, ctypes.c_int32,
             ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_int32, i32p,
         ]
+        h.oracle_tree_attention_extents.restype = ctypes.c_int
+        h.oracle_tree_attention_extents.argtypes = [
+            f32p, f32p, f32p, ctypes.POINTER(ctypes.c_double),
+            i32p, i32p, i32p, i32p, ctypes.c_int32, i32p, ctypes.c_int32, ctypes.c_int32,
+            ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_int32, i32p,
+        ]
         _handle = h
     return _handle
 
@@ -97,4 +103,39 @@ def tree_attention(Q, K, V, node_tok_begin, node_tok_len, node_parent, query_nod
         raise ValueError(f"oracle_tree_attention failed with code {rc}")
     if return_threads:
         return out, int(used.value)
+    return out
+
+
+def tree_attention_paged(Q, K, V, node_page_ptr, page_ids, page_size, node_tok_len, node_parent, query_node,
+                         scale: float | None = None, nthreads: int = 0):
+    """The same attention over a paged pool: K, V are [n_pool_pages * page_size, Hkv, d] and token t of node u
+    is row page_ids[node_page_ptr[u] + t // page_size] * page_size + t % page_size (Section 4.2).  Every page
+    becomes one extent of the node, in order; nothing is merged or moved."""
+    q, k, v = _as_f32(Q), _as_f32(K), _as_f32(V)
+    nq, Hq, d = q.shape
+    ntok, Hkv, _ = k.shape
+    pp, pg, nl, npar, qn = map(_as_i32, (node_page_ptr, page_ids, node_tok_len, node_parent, query_node))
+    P = int(page_size)
+    ext_ptr, ext_begin, ext_len = [0], [], []
+    for u in range(nl.shape[0]):
+        left, i = int(nl[u]), 0
+        while left > 0:
+            ext_begin.append(int(pg[pp[u] + i]) * P)
+            ext_len.append(min(P, left))
+            left -= P
+            i += 1
+        ext_ptr.append(len(ext_len))
+    ep, eb, el = map(_as_i32, (ext_ptr, ext_begin if ext_begin else [0], ext_len if ext_len else [0]))
+    if scale is None:
+        scale = 1.0 / float(np.sqrt(d))
+    out = np.zeros((nq, Hq, d), dtype=np.float64)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    rc = _lib().oracle_tree_attention_extents(
+        q.ctypes.data_as(f32p), k.ctypes.data_as(f32p), v.ctypes.data_as(f32p),
+        out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+        ep.ctypes.data_as(i32p), eb.ctypes.data_as(i32p), el.ctypes.data_as(i32p), npar.ctypes.data_as(i32p),
+        nl.shape[0], qn.ctypes.data_as(i32p), nq, ntok, Hq, Hkv, d, float(scale), int(nthreads), None)
+    if rc != 0:
+        raise ValueError(f"oracle_tree_attention_extents failed with code {rc}")
     return out

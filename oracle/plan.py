@@ -68,14 +68,55 @@ def _validate(nb, nl, par, qn, ntok, chunk_size):
 
 
 def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, chunk_size=128, mode="flatten"):
+    """The plan for a node-contiguous cache: node u owns rows [node_tok_begin[u], +node_tok_len[u])."""
     nb = [int(x) for x in node_tok_begin]
     nl = [int(x) for x in node_tok_len]
     par = [int(x) for x in node_parent]
     qn = [int(x) for x in query_node]
-    ntok = int(ntok)
-    B = int(chunk_size)
-    _validate(nb, nl, par, qn, ntok, B)
-    n, nq = len(nb), len(qn)
+    _validate(nb, nl, par, qn, int(ntok), int(chunk_size))
+    ext = [[(nb[u], nl[u])] if nl[u] > 0 else [] for u in range(len(nb))]
+    return _plan(ext, nl, par, qn, int(chunk_size), mode)
+
+
+def flatten_plan_paged(node_page_ptr, page_ids, page_size, n_pool_pages, node_tok_len, node_parent, query_node,
+                       chunk_size=128, mode="flatten"):
+    """The plan for a paged cache (Section 4.2): token t of node u is row
+    page_ids[node_page_ptr[u] + t // page_size] * page_size + t % page_size.  Pages that follow each other in
+    the pool are joined into one run; segments are cut where a node's storage is not contiguous."""
+    pp = [int(x) for x in node_page_ptr]
+    pg = [int(x) for x in page_ids]
+    nl = [int(x) for x in node_tok_len]
+    par = [int(x) for x in node_parent]
+    qn = [int(x) for x in query_node]
+    P, npool = int(page_size), int(n_pool_pages)
+    n = len(nl)
+    if P < 1 or npool < 0 or len(pp) != n + 1 or pp[0] != 0:
+        raise PlanError("bad page table")
+    ext, seen = [], set()
+    for u in range(n):
+        if nl[u] < 0 or pp[u + 1] < pp[u]:
+            raise PlanError("bad page table")
+        need = -(-nl[u] // P)
+        if pp[u + 1] - pp[u] < need:
+            raise PlanError("node has too few pages")
+        runs = []
+        for i in range(need):
+            page = pg[pp[u] + i]
+            if page < 0 or page >= npool or page in seen:
+                raise PlanError("page out of range or owned twice")
+            seen.add(page)
+            begin, cnt = page * P, min(P, nl[u] - i * P)
+            if runs and runs[-1][0] + runs[-1][1] == begin:
+                runs[-1] = (runs[-1][0], runs[-1][1] + cnt)
+            else:
+                runs.append((begin, cnt))
+        ext.append(runs)
+    _validate([0] * n, [0] * n, par, qn, npool * P, int(chunk_size))   # tree shape, query map, chunk size
+    return _plan(ext, nl, par, qn, int(chunk_size), mode)
+
+
+def _plan(ext, nl, par, qn, B, mode):
+    n, nq = len(nl), len(qn)
 
     # 1. children lists, ascending node id
     children = [[] for _ in range(n)]
@@ -117,6 +158,21 @@ def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, ch
     # 4. flattened sequence: reached, non-empty nodes in preorder
     flat_nodes = [u for u in pre if q_hi[u] > q_lo[u] and nl[u] > 0]
 
+    def node_range(u, off, take):
+        """Physical runs (begin, length) of tokens [off, off+take) of node u."""
+        out, skip = [], off
+        for (b, ln) in ext[u]:
+            if take == 0:
+                break
+            if skip >= ln:
+                skip -= ln
+                continue
+            here = min(take, ln - skip)
+            out.append((b + skip, here))
+            take -= here
+            skip = 0
+        return out
+
     # 5./6. the split: chunks as lists of node pieces (physical begin, length, query interval, node)
     chunks = []
     if mode == "flatten":
@@ -129,7 +185,7 @@ def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, ch
                     chunks.append(cur)
                     cur, room = [], B
                 take = min(room, nl[u] - off)
-                cur.append((nb[u] + off, take, q_lo[u], q_hi[u], u))
+                cur.extend((b, ln, q_lo[u], q_hi[u], u) for (b, ln) in node_range(u, off, take))
                 off += take
                 room -= take
         if cur:
@@ -137,12 +193,12 @@ def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, ch
     elif mode == "node":
         # DeFT-Node (Algorithm 1): one QKV group per tree node, however long
         for u in flat_nodes:
-            chunks.append([(nb[u], nl[u], q_lo[u], q_hi[u], u)])
+            chunks.append([(b, ln, q_lo[u], q_hi[u], u) for (b, ln) in node_range(u, 0, nl[u])])
     elif mode == "node_chunk":
         # DeFT-Node-Chunk (Section 3.3): node-wise grouping, each node cut into blocks of B tokens
         for u in flat_nodes:
             for off in range(0, nl[u], B):
-                chunks.append([(nb[u] + off, min(B, nl[u] - off), q_lo[u], q_hi[u], u)])
+                chunks.append([(b, ln, q_lo[u], q_hi[u], u) for (b, ln) in node_range(u, off, min(B, nl[u] - off))])
     elif mode == "query":
         # Q-guided grouping with the Flash-Decoding split (Section 3.1; Table 2): every query is grouped with
         # its own root-to-node KV, cut into blocks of B tokens; shared prefixes are repeated per query
@@ -160,7 +216,7 @@ def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, ch
                         chunks.append(cur)
                         cur, room = [], B
                     take = min(room, nl[u] - off)
-                    cur.append((nb[u] + off, take, pos, pos + 1, u))
+                    cur.extend((b, ln, pos, pos + 1, u) for (b, ln) in node_range(u, off, take))
                     off += take
                     room -= take
             if cur:

@@ -29,15 +29,20 @@
 #include <omp.h>
 #endif
 
-/* Returns 0 on success; -1 bad argument; -2 malformed tree (cycle / bad index); -3 out of memory. */
-int oracle_tree_attention(const float *Q, const float *K, const float *V, double *O,
-                          const int32_t *node_tok_begin, const int32_t *node_tok_len,
-                          const int32_t *node_parent, int32_t n_nodes,
-                          const int32_t *query_node, int32_t nq, int32_t ntok,
-                          int32_t Hq, int32_t Hkv, int32_t d, double scale, int32_t nthreads,
-                          int32_t *threads_used)
+/*
+ * Core: node u owns extents ext_ptr[u] .. ext_ptr[u+1]-1, each a run of physical rows
+ * [ext_begin, ext_begin + ext_len); its tokens are those runs in order.  A contiguous cache has one
+ * extent per node, a paged cache one per page.
+ * Returns 0 on success; -1 bad argument; -2 malformed tree (cycle / bad index); -3 out of memory.
+ */
+int oracle_tree_attention_extents(const float *Q, const float *K, const float *V, double *O,
+                                  const int32_t *ext_ptr, const int32_t *ext_begin, const int32_t *ext_len,
+                                  const int32_t *node_parent, int32_t n_nodes,
+                                  const int32_t *query_node, int32_t nq, int32_t ntok,
+                                  int32_t Hq, int32_t Hkv, int32_t d, double scale, int32_t nthreads,
+                                  int32_t *threads_used)
 {
-    if (!Q || !K || !V || !O || n_nodes <= 0 || nq < 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || Hq % Hkv != 0)
+    if (!Q || !K || !V || !O || !ext_ptr || n_nodes <= 0 || nq < 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || Hq % Hkv != 0)
         return -1;
     const int group = Hq / Hkv;
     int status = 0;
@@ -66,9 +71,11 @@ int oracle_tree_attention(const float *Q, const float *K, const float *V, double
             int steps = 0, bad = 0;
             for (int u = query_node[j]; u != -1; u = node_parent[u]) {
                 if (u < 0 || u >= n_nodes || ++steps > n_nodes) { bad = 1; break; }
-                if (node_tok_len[u] < 0 || node_tok_begin[u] < 0 ||
-                    (int64_t)node_tok_begin[u] + node_tok_len[u] > ntok) { bad = 1; break; }
-                n += node_tok_len[u];
+                for (int32_t e = ext_ptr[u]; e < ext_ptr[u + 1]; ++e) {
+                    if (ext_len[e] < 0 || ext_begin[e] < 0 || (int64_t)ext_begin[e] + ext_len[e] > ntok) { bad = 1; break; }
+                    n += ext_len[e];
+                }
+                if (bad) break;
             }
             if (bad) {
 #pragma omp atomic write
@@ -89,8 +96,9 @@ int oracle_tree_attention(const float *Q, const float *K, const float *V, double
             }
             int64_t p = 0;
             for (int u = query_node[j]; u != -1; u = node_parent[u])
-                for (int32_t t = 0; t < node_tok_len[u]; ++t)
-                    tok[p++] = (int64_t)node_tok_begin[u] + t;
+                for (int32_t e = ext_ptr[u]; e < ext_ptr[u + 1]; ++e)
+                    for (int32_t t = 0; t < ext_len[e]; ++t)
+                        tok[p++] = (int64_t)ext_begin[e] + t;
 
             const float *q = Q + ((int64_t)j * Hq + h) * d;
             double *o = O + ((int64_t)j * Hq + h) * d;
@@ -121,4 +129,22 @@ int oracle_tree_attention(const float *Q, const float *K, const float *V, double
     }
     if (threads_used) *threads_used = used;
     return status;
+}
+
+/* Node-contiguous cache: node u owns rows [node_tok_begin[u], +node_tok_len[u]). */
+int oracle_tree_attention(const float *Q, const float *K, const float *V, double *O,
+                          const int32_t *node_tok_begin, const int32_t *node_tok_len,
+                          const int32_t *node_parent, int32_t n_nodes,
+                          const int32_t *query_node, int32_t nq, int32_t ntok,
+                          int32_t Hq, int32_t Hkv, int32_t d, double scale, int32_t nthreads,
+                          int32_t *threads_used)
+{
+    if (!node_tok_begin || !node_tok_len || n_nodes <= 0) return -1;
+    int32_t *ptr = (int32_t *)malloc(sizeof(int32_t) * ((size_t)n_nodes + 1));
+    if (!ptr) return -3;
+    for (int32_t u = 0; u <= n_nodes; ++u) ptr[u] = u; /* one extent per node */
+    const int rc = oracle_tree_attention_extents(Q, K, V, O, ptr, node_tok_begin, node_tok_len, node_parent, n_nodes,
+                                                 query_node, nq, ntok, Hq, Hkv, d, scale, nthreads, threads_used);
+    free(ptr);
+    return rc;
 }

@@ -28,7 +28,7 @@ SPLIT_MODES = {"flatten": DEFT_SPLIT_FLATTEN, "node": DEFT_SPLIT_NODE, "node_chu
                "query": DEFT_GROUP_QUERY}
 
 EXPORTS = (
-    "deft_plan", "deft_suggest_chunk_size", "deft_plan_view", "deft_plan_device_bytes", "deft_plan_upload", "deft_workspace_bytes",
+    "deft_plan", "deft_plan_paged", "deft_suggest_chunk_size", "deft_plan_view", "deft_plan_device_bytes", "deft_plan_upload", "deft_workspace_bytes",
     "deft_tree_attn_decode", "deft_stage1_partial_attention", "deft_stage2_global_reduction",
     "deft_plan_destroy", "deft_strerror", "deft_last_hip_error",
 )
@@ -85,6 +85,9 @@ def load_library():
     vp, c32, csz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     lib.deft_plan.restype = ctypes.c_int
     lib.deft_plan.argtypes = [_i32p, _i32p, _i32p, c32, _i32p, c32, c32, c32, ctypes.c_uint32, ctypes.POINTER(vp)]
+    lib.deft_plan_paged.restype = ctypes.c_int
+    lib.deft_plan_paged.argtypes = [_i32p, _i32p, c32, c32, _i32p, _i32p, c32, _i32p, c32, c32, ctypes.c_uint32,
+                                    ctypes.POINTER(vp)]
     lib.deft_suggest_chunk_size.restype = ctypes.c_int32
     lib.deft_suggest_chunk_size.argtypes = [_i32p, _i32p, c32, _i32p, c32, c32, c32]
     lib.deft_plan_view.restype = ctypes.c_int
@@ -227,6 +230,22 @@ def deft_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok: int, 
     rc = lib.deft_plan(nb.ctypes.data_as(_i32p), nl.ctypes.data_as(_i32p), par.ctypes.data_as(_i32p), nb.size,
                        qptr, qn.size, int(ntok), int(chunk_size), int(flags), ctypes.byref(out))
     _check(rc, "deft_plan")
+    return Plan(out)
+
+
+def deft_plan_paged(node_page_ptr, page_ids, page_size: int, n_pool_pages: int, node_tok_len, node_parent,
+                    query_node, chunk_size: int = 0, flags: int = 0) -> Plan:
+    """QKV Preparation Phase over a paged KV pool (K/V are [n_pool_pages * page_size, Hkv, d])."""
+    lib = load_library()
+    pp, pg, nl, par, qn = (_i32(x) for x in (node_page_ptr, page_ids, node_tok_len, node_parent, query_node))
+    if not (nl.size == par.size == pp.size - 1):
+        raise DeftError(-1, "deft_plan_paged: node table columns differ in length")
+    out = ctypes.c_void_p()
+    rc = lib.deft_plan_paged(pp.ctypes.data_as(_i32p), pg.ctypes.data_as(_i32p) if pg.size else None, int(page_size),
+                             int(n_pool_pages), nl.ctypes.data_as(_i32p), par.ctypes.data_as(_i32p), nl.size,
+                             qn.ctypes.data_as(_i32p) if qn.size else None, qn.size, int(chunk_size), int(flags),
+                             ctypes.byref(out))
+    _check(rc, "deft_plan_paged")
     return Plan(out)
 
 

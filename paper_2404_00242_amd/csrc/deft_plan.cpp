@@ -53,11 +53,18 @@ bool preorder(const int32_t *parent, int32_t n, std::vector<int32_t> &order, std
 
 }  // namespace
 
-extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_len, const int32_t *node_parent,
-                         int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size,
-                         uint32_t flags, deft_plan_t **out_plan) {
-    if (out_plan) *out_plan = nullptr;
-    if (!out_plan || !node_tok_begin || !node_tok_len || !node_parent) return DEFT_EINVAL;
+namespace {
+
+// Where a node's tokens live: node u owns extents ext_ptr[u] .. ext_ptr[u+1]-1, each a run of physical rows
+// [begin, begin+len); its tokens are the concatenation of its extents.  A contiguous cache gives one extent
+// per node, a paged cache one per run of consecutive pages.
+struct NodeExtents {
+    std::vector<int32_t> ptr, begin, len;
+};
+
+int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t *node_parent, int32_t n_nodes,
+              const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size, uint32_t flags,
+              deft_plan_t **out_plan) {
     if (n_nodes < 1 || nq < 0 || ntok < 0 || flags > DEFT_GROUP_QUERY) return DEFT_EINVAL;
     const uint32_t mode = flags;
     if (nq > 0 && !query_node) return DEFT_EINVAL;
@@ -71,9 +78,15 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
         for (int32_t u = 0; u < n; ++u) {
             int32_t p = node_parent[u];
             if (p < -1 || p >= n || p == u) return DEFT_EINVAL;
-            int64_t b = node_tok_begin[u], len = node_tok_len[u];
-            if (b < 0 || len < 0 || b + len > (int64_t)ntok) return DEFT_EINVAL;
-            if (len > 0) spans.push_back({b, b + len});
+            if (node_tok_len[u] < 0) return DEFT_EINVAL;
+            int64_t total = 0;
+            for (int32_t e = ext.ptr[u]; e < ext.ptr[u + 1]; ++e) {
+                const int64_t b = ext.begin[e], len = ext.len[e];
+                if (b < 0 || len <= 0 || b + len > (int64_t)ntok) return DEFT_EINVAL;
+                spans.push_back({b, b + len});
+                total += len;
+            }
+            if (total != node_tok_len[u]) return DEFT_EINVAL;
         }
         std::sort(spans.begin(), spans.end(), [](const Range &a, const Range &b) { return a.begin < b.begin; });
         for (size_t i = 1; i < spans.size(); ++i)
@@ -141,6 +154,20 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
         };
         auto close = [&]() { open = false; };
         auto reached = [&](int32_t u) { return P->node_q_hi[u] > P->node_q_lo[u] && node_tok_len[u] > 0; };
+        // tokens [off, off+take) of node u, cut where the node's storage is not contiguous
+        auto node_range = [&](int32_t u, int32_t off, int32_t take, int32_t lo, int32_t hi) {
+            int32_t skip = off;
+            for (int32_t e = ext.ptr[u]; e < ext.ptr[u + 1] && take > 0; ++e) {
+                if (skip >= ext.len[e]) {
+                    skip -= ext.len[e];
+                    continue;
+                }
+                const int32_t here = std::min(take, ext.len[e] - skip);
+                piece(ext.begin[e] + skip, here, lo, hi, u);
+                take -= here;
+                skip = 0;
+            }
+        };
         switch (mode) {
             case DEFT_SPLIT_FLATTEN: {
                 // Flattened Tree KV Splitting (Remark 3.1): depth-first order, a cut every S tokens
@@ -156,7 +183,7 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
                             room = S;
                         }
                         const int32_t take = std::min(room, len - done);
-                        piece(node_tok_begin[u] + done, take, P->node_q_lo[u], P->node_q_hi[u], u);
+                        node_range(u, done, take, P->node_q_lo[u], P->node_q_hi[u]);
                         done += take;
                         room -= take;
                     }
@@ -168,7 +195,7 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
                 for (int32_t i = 0; i < n; ++i) {
                     const int32_t u = pre[i];
                     if (!reached(u)) continue;
-                    piece(node_tok_begin[u], node_tok_len[u], P->node_q_lo[u], P->node_q_hi[u], u);
+                    node_range(u, 0, node_tok_len[u], P->node_q_lo[u], P->node_q_hi[u]);
                     close();
                 }
                 break;
@@ -178,8 +205,7 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
                     const int32_t u = pre[i];
                     if (!reached(u)) continue;
                     for (int32_t done = 0; done < node_tok_len[u]; done += S) {
-                        piece(node_tok_begin[u] + done, std::min(S, node_tok_len[u] - done), P->node_q_lo[u],
-                              P->node_q_hi[u], u);
+                        node_range(u, done, std::min(S, node_tok_len[u] - done), P->node_q_lo[u], P->node_q_hi[u]);
                         close();
                     }
                 }
@@ -200,7 +226,7 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
                                 room = S;
                             }
                             const int32_t take = std::min(room, len - done);
-                            piece(node_tok_begin[u] + done, take, pos, pos + 1, u);
+                            node_range(u, done, take, pos, pos + 1);
                             done += take;
                             room -= take;
                         }
@@ -275,6 +301,68 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
         return DEFT_ENOMEM;
     } catch (...) {
         return DEFT_EINVAL;
+    }
+}
+
+}  // namespace
+
+extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_len, const int32_t *node_parent,
+                         int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size,
+                         uint32_t flags, deft_plan_t **out_plan) {
+    if (out_plan) *out_plan = nullptr;
+    if (!out_plan || !node_tok_begin || !node_tok_len || !node_parent || n_nodes < 1) return DEFT_EINVAL;
+    try {
+        NodeExtents ext;
+        ext.ptr.assign(1, 0);
+        for (int32_t u = 0; u < n_nodes; ++u) {
+            if (node_tok_begin[u] < 0 || node_tok_len[u] < 0 || (int64_t)node_tok_begin[u] + node_tok_len[u] > ntok)
+                return DEFT_EINVAL;
+            if (node_tok_len[u] > 0) {
+                ext.begin.push_back(node_tok_begin[u]);
+                ext.len.push_back(node_tok_len[u]);
+            }
+            ext.ptr.push_back((int32_t)ext.len.size());
+        }
+        return plan_impl(ext, node_tok_len, node_parent, n_nodes, query_node, nq, ntok, chunk_size, flags, out_plan);
+    } catch (const std::bad_alloc &) {
+        return DEFT_ENOMEM;
+    }
+}
+
+extern "C" int deft_plan_paged(const int32_t *node_page_ptr, const int32_t *page_ids, int32_t page_size,
+                               int32_t n_pool_pages, const int32_t *node_tok_len, const int32_t *node_parent,
+                               int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t chunk_size,
+                               uint32_t flags, deft_plan_t **out_plan) {
+    if (out_plan) *out_plan = nullptr;
+    if (!out_plan || !node_page_ptr || !node_tok_len || !node_parent || n_nodes < 1) return DEFT_EINVAL;
+    if (page_size < 1 || n_pool_pages < 0 || (int64_t)page_size * n_pool_pages > INT32_MAX) return DEFT_EINVAL;
+    try {
+        NodeExtents ext;
+        ext.ptr.assign(1, 0);
+        if (node_page_ptr[0] != 0) return DEFT_EINVAL;
+        for (int32_t u = 0; u < n_nodes; ++u) {
+            const int32_t p0 = node_page_ptr[u], p1 = node_page_ptr[u + 1], len = node_tok_len[u];
+            if (p1 < p0 || len < 0) return DEFT_EINVAL;
+            const int64_t need = ((int64_t)len + page_size - 1) / page_size;
+            if (p1 - p0 < need || (need > 0 && !page_ids)) return DEFT_EINVAL;
+            for (int32_t i = 0; i < need; ++i) {
+                const int32_t pg = page_ids[p0 + i];
+                if (pg < 0 || pg >= n_pool_pages) return DEFT_EINVAL;
+                const int32_t begin = pg * page_size, cnt = std::min(page_size, len - i * page_size);
+                // a page that follows the previous one in the pool extends the previous extent
+                if ((int32_t)ext.len.size() > ext.ptr.back() && ext.begin.back() + ext.len.back() == begin)
+                    ext.len.back() += cnt;
+                else {
+                    ext.begin.push_back(begin);
+                    ext.len.push_back(cnt);
+                }
+            }
+            ext.ptr.push_back((int32_t)ext.len.size());
+        }
+        return plan_impl(ext, node_tok_len, node_parent, n_nodes, query_node, nq, n_pool_pages * page_size,
+                         chunk_size, flags, out_plan);
+    } catch (const std::bad_alloc &) {
+        return DEFT_ENOMEM;
     }
 }
 

@@ -172,6 +172,39 @@ def random_tree(seed: int, n_nodes: int = 12, max_len: int = 70, nq: int = 9, Hq
     return _finish(f"random_{seed}", lens, parents, query_node, Hq, Hkv, d, 5000 + seed, begins=begins, ntok=ntok)
 
 
+def to_paged(tree: Tree, page_size: int, seed: int = 0, shuffle: bool = True, spare_pages: int = 3):
+    """Scatters a tree's tokens over a paged pool: every node gets ceil(len / page_size) pages of its own,
+    drawn from the pool in random order (or in node order when shuffle is false), the last one partly filled.
+    Returns (node_page_ptr, page_ids, n_pool_pages, row_of) where row_of[r] is the pool row of row r of the
+    tree's node-contiguous cache (-1 for rows no node owns)."""
+    rng = np.random.default_rng(seed)
+    need = [-(-int(n) // page_size) for n in tree.node_tok_len]
+    total = int(sum(need))
+    n_pool = total + spare_pages
+    order = rng.permutation(n_pool)[:total] if shuffle else np.arange(total)
+    node_page_ptr = np.zeros(tree.n_nodes + 1, dtype=np.int32)
+    node_page_ptr[1:] = np.cumsum(need)
+    page_ids = np.asarray(order, dtype=np.int32)
+    row_of = np.full(tree.ntok, -1, dtype=np.int64)
+    for u in range(tree.n_nodes):
+        b, n = int(tree.node_tok_begin[u]), int(tree.node_tok_len[u])
+        for t in range(n):
+            row_of[b + t] = int(page_ids[node_page_ptr[u] + t // page_size]) * page_size + t % page_size
+    return node_page_ptr, page_ids, n_pool, row_of
+
+
+def scatter_to_pool(x, row_of, n_pool_rows: int, fill_seed: int = 7):
+    """Moves a [ntok, H, d] tensor of a node-contiguous cache into a [n_pool_rows, H, d] pool; rows of the pool
+    that no token owns are filled with other random values (they must never be read)."""
+    import torch
+
+    g = torch.Generator().manual_seed(fill_seed)
+    pool = torch.randn((n_pool_rows,) + tuple(x.shape[1:]), generator=g).to(x.dtype)
+    owned = torch.from_numpy(np.nonzero(row_of >= 0)[0])
+    pool[torch.from_numpy(row_of[row_of >= 0])] = x[owned]
+    return pool
+
+
 def _to_bf16(x: np.ndarray):
     import torch
 
