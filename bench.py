@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--mode", default="flatten", choices=["flatten", "node", "node_chunk", "query"],
                     help="partitioning strategy of the plan (flatten = the paper's method and the headline; the others "
                          "are its ablation / comparison strategies run on the same kernels)")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="0: node-contiguous KV cache (the headline); P > 0: the same tree over a paged pool of "
+                         "P-token pages handed out in random order (deft_plan_paged)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a few plain 1 GiB device-to-device copies (known size) so that a rocprofv3 "
@@ -92,14 +95,25 @@ def main():
     Hq, Hkv, d, L = tree.Hq, tree.Hkv, tree.d, args.layers
     Q0, K0, V0 = workloads.make_qkv(tree)  # layer 0: the seeded workload the parity tests use
 
+    # paged variant: the same tokens scattered over a pool of pages in random order
+    P = args.page_size
+    n_rows = tree.ntok
+    if P > 0:
+        page_ptr, page_ids, n_pool, row_of = workloads.to_paged(tree, P, seed=tree.value_seed)
+        n_rows = n_pool * P
+        K0p = workloads.scatter_to_pool(K0, row_of, n_rows, 1)
+        V0p = workloads.scatter_to_pool(V0, row_of, n_rows, 2)
+    else:
+        K0p, V0p = K0, V0
+
     # per-layer inputs, resident in HBM
     gen = torch.Generator(device=dev)
     gen.manual_seed(tree.value_seed)
-    qs, ks, vs, outs = [Q0.to(dev)], [K0.to(dev)], [V0.to(dev)], []
+    qs, ks, vs, outs = [Q0.to(dev)], [K0p.to(dev)], [V0p.to(dev)], []
     for _ in range(1, L):
         qs.append(torch.randn((tree.nq, Hq, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
-        ks.append(torch.randn((tree.ntok, Hkv, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
-        vs.append(torch.randn((tree.ntok, Hkv, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
+        ks.append(torch.randn((n_rows, Hkv, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
+        vs.append(torch.randn((n_rows, Hkv, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
     for _ in range(L):
         outs.append(torch.empty((tree.nq, Hq, d), device=dev, dtype=torch.bfloat16))
 
@@ -115,7 +129,13 @@ def main():
 
     # sizes are a property of the tree: allocate the image buffer and the workspace once
     mode_flag = binding.SPLIT_MODES[args.mode]
-    probe = binding.deft_plan(nb, nl, par, qn, tree.ntok, args.chunk, mode_flag)
+    if P > 0:
+        ppa = np.ascontiguousarray(page_ptr, dtype=np.int32)
+        pga = np.ascontiguousarray(page_ids, dtype=np.int32)
+        ppp, pgp = ppa.ctypes.data_as(i32p), pga.ctypes.data_as(i32p)
+        probe = binding.deft_plan_paged(ppa, pga, P, n_pool, nl, par, qn, args.chunk, mode_flag)
+    else:
+        probe = binding.deft_plan(nb, nl, par, qn, tree.ntok, args.chunk, mode_flag)
     view = probe.view()
     img_bytes = probe.device_bytes(Hq, Hkv)
     ws_bytes = probe.workspace_bytes(Hq, Hkv, d)
@@ -136,9 +156,12 @@ def main():
         h = vp()
         if lib.deft_suggest_chunk_size(nlp, parp, tree.n_nodes, qnp, tree.nq, Hq, Hkv) < 0:
             raise RuntimeError("deft_suggest_chunk_size failed")
-        check(lib.deft_plan(nbp, nlp, parp, tree.n_nodes, qnp, tree.nq, tree.ntok, args.chunk, mode_flag,
-                            ctypes.byref(h)),
-              "deft_plan")
+        if P > 0:
+            check(lib.deft_plan_paged(ppp, pgp, P, n_pool, nlp, parp, tree.n_nodes, qnp, tree.nq, args.chunk, mode_flag,
+                                      ctypes.byref(h)), "deft_plan_paged")
+        else:
+            check(lib.deft_plan(nbp, nlp, parp, tree.n_nodes, qnp, tree.nq, tree.ntok, args.chunk, mode_flag,
+                                ctypes.byref(h)), "deft_plan")
         if lib.deft_plan_device_bytes(h, Hq, Hkv) > img_bytes:
             raise RuntimeError("plan image grew")
         check(lib.deft_plan_upload(h, Hq, Hkv, imgp, img_bytes, st), "deft_plan_upload")
@@ -213,7 +236,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": workload, "split": args.mode, "Hq": Hq, "Hkv": Hkv, "d": d, "ntok": tree.ntok, "nq": tree.nq,
+            "workload": workload, "split": args.mode, "page_size": P, "Hq": Hq, "Hkv": Hkv, "d": d, "ntok": tree.ntok, "nq": tree.nq,
             "layers_per_step": L, "chunk_size": view["chunk_size"], "n_chunks": view["n_chunks"],
             "n_slots": view["n_slots"], "path_tokens": workloads.path_token_count(tree),
         },
@@ -226,7 +249,7 @@ def main():
             "kernel": "deft_stage1 (partial attention, one layer-call)",
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": kv_bytes,
-            "traffic": traffic_from_profiles(workload) if args.mode == "flatten" else None,
+            "traffic": traffic_from_profiles(workload) if args.mode == "flatten" and P == 0 else None,
         },
     }
 
