@@ -215,6 +215,32 @@ def main():
     s1_us = float(np.mean(s1_ms)) * 1e3
     s2_us = float(np.mean(s2_ms)) * 1e3
 
+    # the same call with one replica only (layer 0 every time): the memory-side cache then holds part of K/V
+    ew0, ew1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    qp, kp, vpp, op = layer_ptrs[0]
+    spare = torch.empty_like(outs[0])
+    ew0.record(stream)
+    for _ in range(L):
+        lib.deft_tree_attn_decode(h, imgp, qp, kp, vpp, vp(spare.data_ptr()), Hq, Hkv, d, 0.0, 0, wsp, ws_bytes, st)
+    ew1.record(stream)
+    torch.cuda.synchronize()
+    warm_us = ew0.elapsed_time(ew1) / L * 1e3
+
+    # read-stream ceiling of this machine: every layer's K and V read once by a plain 128-bit-load kernel
+    sink = torch.zeros(2048, dtype=torch.int32, device=dev)
+    buf_bytes = ks[0].numel() * 2
+    probe_ms = []
+    for _ in range(3):
+        ep0, ep1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ep0.record(stream)
+        for i in range(L):
+            check(lib.deft_hbm_read_probe(vp(ks[i].data_ptr()), buf_bytes, vp(sink.data_ptr()), st), "deft_hbm_read_probe")
+            check(lib.deft_hbm_read_probe(vp(vs[i].data_ptr()), buf_bytes, vp(sink.data_ptr()), st), "deft_hbm_read_probe")
+        ep1.record(stream)
+        torch.cuda.synchronize()
+        probe_ms.append(ep0.elapsed_time(ep1))
+    stream_gbs = 2 * L * buf_bytes / (min(probe_ms[1:]) * 1e-3) / 1e9
+
     # K and V of every reached token, once per KV head: what the method itself must move (a Q-guided plan
     # moves more, but the useful bytes stay these)
     n_reached = int(sum(int(nl[u]) for u in set(int(x) for x in view["seg_node"])))
@@ -244,11 +270,13 @@ def main():
         "kv_frac_of_peak_whole_call": round(kv_bytes / (us_per_call * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
         "stage1_us": round(s1_us, 3),
         "stage2_us": round(s2_us, 3),
+        "warm_single_replica_us": round(warm_us, 3),
         "plan_plus_upload_us": round(plan_us, 1),
         "roofline": {
             "kernel": "deft_stage1 (partial attention, one layer-call)",
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": kv_bytes,
+            "read_stream_ceiling": round(stream_gbs, 1), "frac_of_read_stream": round(achieved / stream_gbs, 4),
             "traffic": traffic_from_profiles(workload) if args.mode == "flatten" and P == 0 else None,
         },
     }

@@ -229,6 +229,18 @@ int deft_stage2_global_reduction(const deft_plan_t *plan, const void *dev_image,
                                  int32_t d, float scale, uint32_t flags, void *workspace, size_t workspace_bytes,
                                  void *stream);
 
+/*
+ * Measurement aid: reads `bytes` bytes at dev_buf once with 128-bit loads from every compute unit
+ * (DEFT_PROBE_SINK_BYTES / 4 workgroups, grid-stride) and stores, for each workgroup, the xor of the
+ * 32-bit words it read into dev_sink (device, DEFT_PROBE_SINK_BYTES bytes, 4-byte aligned; all of it is
+ * overwritten), so the xor over the sink is the xor over the buffer.  The rate it reaches is the
+ * read-stream ceiling against which the benchmark states the KV read rate of stage 1 (the method is
+ * bound by reading the KV cache: Section 3.3, Table 12).  bytes must be a positive multiple of 16 and
+ * dev_buf 16-byte aligned (DEFT_EINVAL otherwise); asynchronous on `stream`.
+ */
+#define DEFT_PROBE_SINK_BYTES 8192
+int deft_hbm_read_probe(const void *dev_buf, size_t bytes, void *dev_sink, void *stream);
+
 void deft_plan_destroy(deft_plan_t *plan);
 
 const char *deft_strerror(int status);

@@ -697,6 +697,26 @@ __global__ __launch_bounds__(64) void deft_stage2(Stage2Args a) {
     }
 }
 
+// Plain read of a buffer with 128-bit loads, every byte once, all compute units busy: the rate this
+// reaches is the practical ceiling for a kernel whose job is to read HBM (Section 3.3's premise is that
+// the KV read dominates).  Workgroup b leaves the xor of the words it read in sink[b], so that no load
+// can be dropped and a caller can check that every word was read exactly once.
+constexpr int kProbeGroups = DEFT_PROBE_SINK_BYTES / 4;
+
+__global__ __launch_bounds__(256) void deft_read_probe(const u32x4 *__restrict__ p, size_t n16, uint32_t *sink) {
+    __shared__ uint32_t part[4];
+    size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const size_t stride = size_t(gridDim.x) * blockDim.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i < n16; i += stride) acc ^= p[i];
+    uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x ^= __shfl_xor(x, off, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = x;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+
 thread_local std::string g_hip_error;
 
 bool hip_ok(hipError_t e, const char *what) {
@@ -828,6 +848,14 @@ int run_stage2(const deft_plan_t *plan, const Call &call, void *o, int32_t Hq, i
 }  // namespace
 
 extern "C" const char *deft_last_hip_error(void) { return g_hip_error.c_str(); }
+
+extern "C" int deft_hbm_read_probe(const void *dev_buf, size_t bytes, void *dev_sink, void *stream) {
+    if (!dev_buf || !dev_sink || bytes == 0 || (bytes & 15) || (reinterpret_cast<uintptr_t>(dev_buf) & 15)) return DEFT_EINVAL;
+    const size_t n16 = bytes / 16;
+    hipLaunchKernelGGL(deft_read_probe, dim3(kProbeGroups), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u32x4 *>(dev_buf), n16, static_cast<uint32_t *>(dev_sink));
+    return hip_ok(hipGetLastError(), "deft_read_probe launch") ? DEFT_OK : DEFT_EHIP;
+}
 
 extern "C" int deft_plan_upload(deft_plan_t *plan, int32_t Hq, int32_t Hkv, void *dev_image, size_t bytes, void *stream) {
     if (!plan || !dev_image || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return DEFT_EINVAL;

@@ -244,3 +244,25 @@ def test_error_paths_do_not_launch():
                                    v.data_ptr(), o.data_ptr(), 4, 4, 96, 0.0, 0, ws.data_ptr(), ws.numel(), None)
     assert rc == -1
     torch.cuda.synchronize()
+
+
+def test_read_probe_reads_every_word_once():
+    """The read-stream probe leaves the xor of every 32-bit word of the buffer in its sink (so no load can have been
+    skipped), for a buffer that is not a multiple of the grid and for a tiny one; bad sizes are refused."""
+    import ctypes
+
+    lib = binding.load_library()
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    g = torch.Generator().manual_seed(11)
+    for n_words in (4, 4 * 1000 + 4, 4 * (1 << 20) + 12):
+        n_words -= n_words % 4
+        host = torch.randint(-2**31, 2**31 - 1, (n_words,), generator=g, dtype=torch.int32)
+        buf = host.cuda()
+        sink = torch.full((2048,), 77, dtype=torch.int32, device="cuda")
+        rc = lib.deft_hbm_read_probe(ctypes.c_void_p(buf.data_ptr()), n_words * 4, ctypes.c_void_p(sink.data_ptr()), st)
+        assert rc == 0
+        torch.cuda.synchronize()
+        want = int(np.bitwise_xor.reduce(host.numpy().view(np.uint32)))
+        assert int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))) == want
+    assert lib.deft_hbm_read_probe(ctypes.c_void_p(buf.data_ptr()), 24, ctypes.c_void_p(sink.data_ptr()), st) == -1
+    assert lib.deft_hbm_read_probe(None, 16, ctypes.c_void_p(sink.data_ptr()), st) == -1
