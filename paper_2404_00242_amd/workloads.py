@@ -230,3 +230,76 @@ def path_token_count(tree: Tree) -> int:
             total += int(tree.node_tok_len[u])
             u = int(tree.node_parent[u])
     return total
+
+
+class DecodeLoopSim:
+    """A decoding tree that changes every iteration, over a paged pool, as in tree-based decoding
+    (Section 2 and Appendix A.1 of the paper: every live leaf generates a token per iteration, the branch
+    controller now and then forks a leaf into several children or prunes branches).
+
+    Only structure is simulated (no values, no arithmetic of the method): nodes own pages of a pool handed out
+    from a shuffled free list; a pruned branch gives its pages back, so later nodes reuse them.  `tables()`
+    returns the current (node_page_ptr, page_ids, node_tok_len, node_parent, query_node) in the form
+    deft_plan_paged takes; nodes are never renumbered, pruned ones just keep no query below them.
+    """
+
+    def __init__(self, seed: int, prompt_len: int, width: int, page_size: int, n_pool_pages: int):
+        self.rng = np.random.default_rng(seed)
+        self.P = page_size
+        self.n_pool = n_pool_pages
+        self.free = list(self.rng.permutation(n_pool_pages))
+        self.pages, self.lens, self.parent = [], [], []
+        self.leaves = []  # live leaves, each carries one query
+        root = self._new_node(-1, prompt_len)
+        for _ in range(width):
+            self.leaves.append(self._new_node(root, 1))
+
+    def _grow(self, u: int, n: int):
+        need = -(-(self.lens[u] + n) // self.P) - len(self.pages[u])
+        if need > len(self.free):
+            raise RuntimeError("pool exhausted")
+        for _ in range(need):
+            self.pages[u].append(int(self.free.pop()))
+        self.lens[u] += n
+
+    def _new_node(self, parent: int, n: int) -> int:
+        self.pages.append([])
+        self.lens.append(0)
+        self.parent.append(parent)
+        u = len(self.lens) - 1
+        self._grow(u, n)
+        return u
+
+    def step(self):
+        """Every live leaf appends the token it generated."""
+        for u in self.leaves:
+            self._grow(u, 1)
+
+    def branch(self, fanout: int = 2):
+        """A random live leaf forks: `fanout` children of one token each take over its query."""
+        i = int(self.rng.integers(len(self.leaves)))
+        u = self.leaves.pop(i)
+        for _ in range(fanout):
+            self.leaves.append(self._new_node(u, 1))
+
+    def prune(self, n: int = 1):
+        """Drops n random live leaves; nodes that no live leaf descends from give their pages back."""
+        for _ in range(min(n, len(self.leaves) - 1)):
+            self.leaves.pop(int(self.rng.integers(len(self.leaves))))
+        alive = set()
+        for u in self.leaves:
+            while u >= 0 and u not in alive:
+                alive.add(u)
+                u = self.parent[u]
+        for u in range(len(self.lens)):
+            if u not in alive and self.pages[u]:
+                self.free.extend(self.pages[u])
+                self.pages[u] = []
+                self.lens[u] = 0
+
+    def tables(self):
+        ptr = np.zeros(len(self.lens) + 1, dtype=np.int32)
+        ptr[1:] = np.cumsum([len(p) for p in self.pages])
+        ids = np.asarray([x for p in self.pages for x in p], dtype=np.int32)
+        return (ptr, ids, np.asarray(self.lens, dtype=np.int32), np.asarray(self.parent, dtype=np.int32),
+                np.asarray(self.leaves, dtype=np.int32))
