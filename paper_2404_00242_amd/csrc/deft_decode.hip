@@ -419,7 +419,12 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     const int n16 = lane & 15;
     const int g = lane >> 4;
     const int item = blockIdx.x / a.Hkv;
-    const int h = blockIdx.x - item * a.Hkv;
+    // KV head of this workgroup.  Workgroups b and b + 256 land on the same compute unit (the dispatcher goes
+    // round the 256 units), and with Hkv dividing 256 they would stream the same head: K and V rows whose
+    // addresses agree in bits 7..12.  A unit whose streams all share those bits reads measurably slower (its
+    // L1 keeps fewer lines in flight), so every further round of 256 workgroups is moved on by one head.
+    // The shift depends on the task only, so a task still visits every head exactly once.
+    const int h = (blockIdx.x - item * a.Hkv + ((item * a.Hkv) >> 8)) % a.Hkv;
     const int32_t *it = a.items + (size_t)item * deft::kItemInts;
     const int tile0 = it[deft::kItTile0], ntiles = it[deft::kItNTiles];
     const int seg0 = it[deft::kItSeg0], nseg = it[deft::kItNSeg];
