@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--page-size", type=int, default=0,
                     help="0: node-contiguous KV cache (the headline); P > 0: the same tree over a paged pool of "
                          "P-token pages handed out in random order (deft_plan_paged)")
+    ap.add_argument("--plain-alloc", action="store_true",
+                    help="allocate every K and V pool with torch.empty (same alignment for both) instead of "
+                         "binding.alloc_kv_cache, which staggers the V pool by half a KiB")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a few plain 1 GiB device-to-device copies (known size) so that a rocprofv3 "
@@ -109,11 +112,25 @@ def main():
     # per-layer inputs, resident in HBM
     gen = torch.Generator(device=dev)
     gen.manual_seed(tree.value_seed)
-    qs, ks, vs, outs = [Q0.to(dev)], [K0p.to(dev)], [V0p.to(dev)], []
-    for _ in range(1, L):
-        qs.append(torch.randn((tree.nq, Hq, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
-        ks.append(torch.randn((n_rows, Hkv, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
-        vs.append(torch.randn((n_rows, Hkv, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
+    def kv_pools():
+        if args.plain_alloc:
+            return (torch.empty((n_rows, Hkv, d), device=dev, dtype=torch.bfloat16),
+                    torch.empty((n_rows, Hkv, d), device=dev, dtype=torch.bfloat16))
+        return binding.alloc_kv_cache(n_rows, Hkv, d, dev)
+
+    qs, ks, vs, outs = [], [], [], []
+    for i in range(L):
+        k, v = kv_pools()
+        if i == 0:
+            qs.append(Q0.to(dev))
+            k.copy_(K0p)
+            v.copy_(V0p)
+        else:
+            qs.append(torch.randn((tree.nq, Hq, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
+            k.copy_(torch.randn((n_rows, Hkv, d), generator=gen, device=dev, dtype=torch.float32))
+            v.copy_(torch.randn((n_rows, Hkv, d), generator=gen, device=dev, dtype=torch.float32))
+        ks.append(k)
+        vs.append(v)
     for _ in range(L):
         outs.append(torch.empty((tree.nq, Hq, d), device=dev, dtype=torch.bfloat16))
 
@@ -262,7 +279,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": workload, "split": args.mode, "page_size": P, "Hq": Hq, "Hkv": Hkv, "d": d, "ntok": tree.ntok, "nq": tree.nq,
+            "workload": workload, "split": args.mode, "page_size": P,
+            "kv_placement": "plain" if args.plain_alloc else "V pool %d B past K pool's alignment (mod 1 KiB)" % binding.KV_STAGGER_BYTES, "Hq": Hq, "Hkv": Hkv, "d": d, "ntok": tree.ntok, "nq": tree.nq,
             "layers_per_step": L, "chunk_size": view["chunk_size"], "n_chunks": view["n_chunks"],
             "n_slots": view["n_slots"], "path_tokens": workloads.path_token_count(tree),
         },

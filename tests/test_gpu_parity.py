@@ -266,3 +266,19 @@ def test_read_probe_reads_every_word_once():
         assert int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))) == want
     assert lib.deft_hbm_read_probe(ctypes.c_void_p(buf.data_ptr()), 24, ctypes.c_void_p(sink.data_ptr()), st) == -1
     assert lib.deft_hbm_read_probe(None, 16, ctypes.c_void_p(sink.data_ptr()), st) == -1
+
+
+def test_staggered_kv_pools_are_placed_as_documented_and_decode_the_same():
+    t = wl.config1_tiny()
+    Q, K, V = wl.make_qkv(t)
+    k, v = binding.alloc_kv_cache(t.ntok, t.Hkv, t.d)
+    assert k.shape == v.shape == (t.ntok, t.Hkv, t.d) and k.dtype == v.dtype == torch.bfloat16
+    assert k.data_ptr() % 1024 == 0 and v.data_ptr() % 1024 == binding.KV_STAGGER_BYTES
+    assert v.data_ptr() >= k.data_ptr() + k.numel() * 2  # no overlap
+    k.copy_(K)
+    v.copy_(V)
+    plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, 128)
+    a = binding.deft_tree_attn_decode(plan, Q.cuda(), k, v)
+    b = binding.deft_tree_attn_decode(plan, Q.cuda(), K.cuda(), V.cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
