@@ -644,42 +644,69 @@ __global__ __launch_bounds__(64) void deft_stage2(Stage2Args a) {
     const int qh = blockIdx.x - p * a.Hq;
     const int s0 = a.q_part_ptr[p];
     const int n = a.q_part_ptr[p + 1] - s0;
+    const int q_user = a.q_order[p];  // fetched with the pointers, not after the sums
     const int sub = lane / LPR, col = lane - sub * LPR;
-
-    float mx = -INFINITY;
-    for (int i = lane; i < n; i += 64) mx = fmaxf(mx, a.part_m[(size_t)a.q_part_slot[s0 + i] * a.Hq + qh]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float lsum = 0.f;
-    if (mx != -INFINITY) {
-        for (int base = 0; base < n; base += 64) {
-            const int i = base + lane;
-            float w = 0.f;
-            int slot = 0;
-            if (i < n) {
-                slot = a.q_part_slot[s0 + i];
-                const size_t ro = (size_t)slot * a.Hq + qh;
-                w = __builtin_amdgcn_exp2f((a.part_m[ro] - mx) * a.c);
-                lsum += w * a.part_l[ro];
-            }
-            const int cnt = min(64, n - base);
-            for (int j = 0; j < cnt; j += 4 * RPI) {
-                // four independent row loads per trip; rows past cnt get weight 0 and read slot 0, which exists
-                float wj[4];
-                f32x4 x[4];
+    constexpr int FAST = 8 * RPI;  // rows a wave can hold in registers
+    if (n > 0 && n <= FAST) {
+        // few partials (the usual case): slot ids in one round trip, then m, l and every row in a second one;
+        // the weights are applied to rows that are already in registers
+        const int slot = lane < n ? a.q_part_slot[s0 + lane] : 0;
+        const size_t ro = (size_t)slot * a.Hq + qh;
+        const float mj = lane < n ? a.part_m[ro] : -INFINITY;
+        const float lj = lane < n ? a.part_l[ro] : 0.f;
+        f32x4 x[8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int jj = j + u * RPI + sub;
-                    const float ws = __shfl(w, jj & 63);
-                    const int sj = __shfl(slot, jj & 63);
-                    wj[u] = jj < cnt ? ws : 0.f;
-                    const int sr = jj < cnt ? sj : 0;
-                    x[u] = *reinterpret_cast<const f32x4 *>(a.part_acc + ((size_t)sr * a.Hq + qh) * D + 4 * col);
+        for (int u = 0; u < 8; ++u) {
+            const int jj = u * RPI + sub;
+            const int sj = __shfl(slot, jj);  // lanes >= n hold slot 0, which exists
+            x[u] = *reinterpret_cast<const f32x4 *>(a.part_acc + ((size_t)sj * a.Hq + qh) * D + 4 * col);
+        }
+        float mx = mj;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        const float w = (lane < n && mx != -INFINITY) ? __builtin_amdgcn_exp2f((mj - mx) * a.c) : 0.f;
+        lsum = w * lj;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float wu = __shfl(w, u * RPI + sub);
+            acc += wu * x[u];
+        }
+    } else if (n > 0) {
+        float mx = -INFINITY;
+        for (int i = lane; i < n; i += 64) mx = fmaxf(mx, a.part_m[(size_t)a.q_part_slot[s0 + i] * a.Hq + qh]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        if (mx != -INFINITY) {
+            for (int base = 0; base < n; base += 64) {
+                const int i = base + lane;
+                float w = 0.f;
+                int slot = 0;
+                if (i < n) {
+                    slot = a.q_part_slot[s0 + i];
+                    const size_t ro = (size_t)slot * a.Hq + qh;
+                    w = __builtin_amdgcn_exp2f((a.part_m[ro] - mx) * a.c);
+                    lsum += w * a.part_l[ro];
                 }
+                const int cnt = min(64, n - base);
+                for (int j = 0; j < cnt; j += 4 * RPI) {
+                    // four independent row loads per trip; rows past cnt get weight 0 and read slot 0, which exists
+                    float wj[4];
+                    f32x4 x[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) acc += wj[u] * x[u];
+                    for (int u = 0; u < 4; ++u) {
+                        const int jj = j + u * RPI + sub;
+                        const float ws = __shfl(w, jj & 63);
+                        const int sj = __shfl(slot, jj & 63);
+                        wj[u] = jj < cnt ? ws : 0.f;
+                        const int sr = jj < cnt ? sj : 0;
+                        x[u] = *reinterpret_cast<const f32x4 *>(a.part_acc + ((size_t)sr * a.Hq + qh) * D + 4 * col);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) acc += wj[u] * x[u];
+                }
             }
         }
     }
@@ -692,7 +719,7 @@ __global__ __launch_bounds__(64) void deft_stage2(Stage2Args a) {
     for (int o = 32; o > 0; o >>= 1) lsum += __shfl_xor(lsum, o);
     if (sub != 0) return;
     const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
-    const size_t oo = ((size_t)a.q_order[p] * a.Hq + qh) * D + 4 * col;
+    const size_t oo = ((size_t)q_user * a.Hq + qh) * D + 4 * col;
     if (a.out_f32) {
         *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.out) + oo) = acc * inv;
     } else {
