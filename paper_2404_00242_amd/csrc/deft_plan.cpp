@@ -498,6 +498,24 @@ static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
         }
     }
 
+    // Dispatch order: workgroups are handed to compute units in the order of the task list, a new one
+    // whenever a slot frees, so the longest tasks go first (tokens x (2 + row tiles) as the estimate) and
+    // the short ones fill the tail.  Equal estimates keep their chunk order, which leaves the row groups of
+    // one chunk next to each other (they re-read that chunk from the same L2).
+    {
+        const int32_t n = (int32_t)(items.size() / kItemInts);
+        std::vector<int32_t> order(n);
+        for (int32_t i = 0; i < n; ++i) order[i] = i;
+        auto cost = [&](int32_t i) {
+            return (int64_t)items[(size_t)i * kItemInts + kItLen] * (2 + items[(size_t)i * kItemInts + kItNTiles]);
+        };
+        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return cost(x) > cost(y); });
+        std::vector<int32_t> sorted(items.size());
+        for (int32_t i = 0; i < n; ++i)
+            std::memcpy(&sorted[(size_t)i * kItemInts], &items[(size_t)order[i] * kItemInts], kItemInts * sizeof(int32_t));
+        items.swap(sorted);
+    }
+
     size_t off = 0;
     auto place = [&](size_t count) {
         size_t at = off;
