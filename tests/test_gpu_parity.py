@@ -282,3 +282,16 @@ def test_staggered_kv_pools_are_placed_as_documented_and_decode_the_same():
     b = binding.deft_tree_attn_decode(plan, Q.cuda(), K.cuda(), V.cuda())
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(6, 3, 128), (5, 5, 64), (14, 7, 128), (24, 24, 64)])
+def test_head_counts_that_do_not_divide_the_dispatch_round(Hq, Hkv, d):
+    """More than 256 workgroups with a KV-head count that does not divide 256: the head a workgroup takes is
+    moved on per dispatch round, and every (task, head) pair must still be visited exactly once."""
+    n_leaves = 120
+    t = wl._finish("many_tasks", [3000] + [33] * n_leaves, [-1] + [0] * n_leaves, list(range(1, n_leaves + 1)),
+                   Hq, Hkv, d, 91)
+    Q, K, V = wl.make_qkv(t)
+    got, plan = run_gpu(t, Q, K, V, chunk_size=32, out_dtype=torch.float32)
+    assert plan.view()["n_chunks"] * Hkv > 512
+    check(got, reference(t, Q, K, V), strict=False)
