@@ -55,7 +55,7 @@ struct Stage1Args {
 
 struct Stage2Args {
     const float *part_acc, *part_m, *part_l;
-    const int32_t *q_order, *q_part_ptr, *q_part_slot;
+    const int32_t *q_head, *q_part_ptr, *q_part_slot;
     void *out;
     int32_t nq, Hq, out_f32;
     float c;
@@ -642,18 +642,20 @@ __global__ __launch_bounds__(64) void deft_stage2(Stage2Args a) {
     const int lane = threadIdx.x;
     const int p = blockIdx.x / a.Hq;
     const int qh = blockIdx.x - p * a.Hq;
-    const int s0 = a.q_part_ptr[p];
-    const int n = a.q_part_ptr[p + 1] - s0;
-    const int q_user = a.q_order[p];  // fetched with the pointers, not after the sums
+    // one 64-byte record per query: how many partials, where the result goes, the first slot ids
+    const int hd = a.q_head[(size_t)p * deft::kQueryHeadInts + (lane & (deft::kQueryHeadInts - 1))];
+    const int n = __shfl(hd, 0);
+    const int q_user = __shfl(hd, 1);
     const int sub = lane / LPR, col = lane - sub * LPR;
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float lsum = 0.f;
-    constexpr int FAST = 8 * RPI;  // rows a wave can hold in registers
+    constexpr int FAST = 8 * RPI < deft::kQueryInlineSlots ? 8 * RPI : deft::kQueryInlineSlots;  // rows held in registers
     if (n > 0 && n <= FAST) {
-        // few partials (the usual case): slot ids in one round trip, then m, l and every row in a second one;
-        // the weights are applied to rows that are already in registers
-        const int slot = lane < n ? a.q_part_slot[s0 + lane] : 0;
+        // few partials (the usual case): the slot ids came with the record, so m, l and every row are
+        // fetched in the next round trip and the weights are applied to rows that are already in registers
+        const int slot_all = __shfl(hd, (lane < n ? lane : 0) + 2);
+        const int slot = lane < n ? slot_all : 0;
         const size_t ro = (size_t)slot * a.Hq + qh;
         const float mj = lane < n ? a.part_m[ro] : -INFINITY;
         const float lj = lane < n ? a.part_l[ro] : 0.f;
@@ -675,6 +677,7 @@ __global__ __launch_bounds__(64) void deft_stage2(Stage2Args a) {
             acc += wu * x[u];
         }
     } else if (n > 0) {
+        const int s0 = a.q_part_ptr[p];
         float mx = -INFINITY;
         for (int i = lane; i < n; i += 64) mx = fmaxf(mx, a.part_m[(size_t)a.q_part_slot[s0 + i] * a.Hq + qh]);
 #pragma unroll
@@ -865,7 +868,7 @@ int run_stage2(const deft_plan_t *plan, const Call &call, void *o, int32_t Hq, i
     a2.part_acc = call.acc;
     a2.part_m = call.pm;
     a2.part_l = call.pl;
-    a2.q_order = at(S.off_q_order);
+    a2.q_head = at(S.off_q_head);
     a2.q_part_ptr = at(S.off_q_part_ptr);
     a2.q_part_slot = at(S.off_q_part_slot);
     a2.out = o;

@@ -16,6 +16,10 @@ namespace deft {
 // without touching any other table.
 constexpr int kItemInts = 16;
 constexpr int kMaxTilesPerTask = 8;
+// Stage 2 reads one kQueryHeadInts-int32 record per plan query: {number of partials n, caller's query index,
+// the first kQueryInlineSlots slot ids}; queries with more partials go on to the CSR lists.
+constexpr int kQueryHeadInts = 16;
+constexpr int kQueryInlineSlots = kQueryHeadInts - 2;
 enum ItemField {
     kItChunk = 0,     // chunk id
     kItTile0 = 1,     // first 16-row tile of the chunk's group handled by this task
@@ -39,6 +43,7 @@ struct Schedule {
     size_t off_seg_tok_begin = 0, off_seg_len = 0, off_seg_qlo = 0, off_seg_qhi = 0, off_seg_off = 0;
     size_t off_q_order = 0;
     size_t off_q_part_ptr = 0, off_q_part_slot = 0;
+    size_t off_q_head = 0;    // per-query records for stage 2
     size_t off_items = 0;     // task descriptors
     int32_t n_items = 0;
     int32_t table_len = 32;   // longest chunk made of several pieces, rounded up to whole blocks: LDS table size

@@ -531,7 +531,8 @@ static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
     S.off_q_order = place(nq);
     S.off_q_part_ptr = place(nq + 1);
     S.off_q_part_slot = place(slots);
-    off = (off + 63) & ~(size_t)63;  // descriptors are aligned 64-byte records
+    off = (off + 63) & ~(size_t)63;  // per-query records and descriptors are aligned 64-byte records
+    S.off_q_head = place((size_t)nq * kQueryHeadInts);
     S.n_items = (int32_t)(items.size() / kItemInts);
     S.off_items = place(items.size());
     S.bytes = std::max<size_t>(off, 16);
@@ -548,6 +549,17 @@ static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
     put(S.off_q_part_ptr, P->q_part_ptr);
     put(S.off_q_part_slot, P->q_part_slot);
     put(S.off_items, items);
+    {
+        std::vector<int32_t> head((size_t)nq * kQueryHeadInts, 0);
+        for (int32_t p = 0; p < nq; ++p) {
+            int32_t *r = &head[(size_t)p * kQueryHeadInts];
+            const int32_t s0 = P->q_part_ptr[p], n = P->q_part_ptr[p + 1] - s0;
+            r[0] = n;
+            r[1] = P->q_order[p];
+            for (int32_t k = 0; k < kQueryInlineSlots && k < n; ++k) r[2 + k] = P->q_part_slot[s0 + k];
+        }
+        put(S.off_q_head, head);
+    }
 }
 
 const Schedule *get_schedule(const deft_plan_t *plan, int32_t group) {
