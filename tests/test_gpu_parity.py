@@ -295,3 +295,27 @@ def test_head_counts_that_do_not_divide_the_dispatch_round(Hq, Hkv, d):
     got, plan = run_gpu(t, Q, K, V, chunk_size=32, out_dtype=torch.float32)
     assert plan.view()["n_chunks"] * Hkv > 512
     check(got, reference(t, Q, K, V), strict=False)
+
+
+def test_rows_beyond_four_gigabytes_are_addressed_correctly():
+    """KV pools larger than 4 GiB: the rows of the far node start 4.5 GB into each pool.  The oracle runs on a
+    compact cache holding the same tokens (moving nodes leaves the attention unchanged)."""
+    Hq, Hkv, d = 32, 32, 128
+    n_rows = 600_000                       # x 8 KiB per row = 4.9 GB per pool
+    lens = [150, 300, 40]
+    begins_far = [10, 550_000, 599_950]    # root near the start, the others beyond 2^32 bytes
+    parents = [-1, 0, 1]
+    qn = [2, 1, 2]
+    compact = wl._finish("compact", lens, parents, qn, Hq, Hkv, d, 123)
+    Q, K, V = wl.make_qkv(compact)
+    ref = reference(compact, Q, K, V)
+    k = torch.empty((n_rows, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    v = torch.empty((n_rows, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    for u in range(3):
+        b0, n = int(compact.node_tok_begin[u]), lens[u]
+        k[begins_far[u]:begins_far[u] + n] = K[b0:b0 + n].cuda()
+        v[begins_far[u]:begins_far[u] + n] = V[b0:b0 + n].cuda()
+    plan = binding.deft_plan(begins_far, lens, parents, qn, n_rows, 64)
+    got = binding.deft_tree_attn_decode(plan, Q.cuda(), k, v, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check(got.cpu().numpy().astype(np.float64), ref, strict=False)
