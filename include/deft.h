@@ -204,7 +204,9 @@ size_t deft_workspace_bytes(const deft_plan_t *plan, int32_t Hq, int32_t Hkv, in
  * scale     : softmax scale; <= 0 selects 1/sqrt(d).
  * workspace : device memory of at least deft_workspace_bytes(plan, Hq, Hkv, d), 16-byte
  *             aligned; contents are scratch.
- * stream    : hipStream_t (NULL = default stream).  Kernels are enqueued, not awaited.
+ * stream    : hipStream_t (NULL = default stream).  Kernels are enqueued, not awaited.  After one
+ *             ordinary call on the device (which sets a kernel attribute), a call made while the
+ *             stream is being captured records just its two kernel launches in the graph.
  * Errors: DEFT_EINVAL, DEFT_ENOTREADY, DEFT_EWORKSPACE, DEFT_EHIP (deft_last_hip_error
  * gives the runtime's text).  Nothing is launched when an error is returned, except that a
  * launch failure may leave earlier kernels of the same call enqueued.

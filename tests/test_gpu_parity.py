@@ -319,3 +319,50 @@ def test_rows_beyond_four_gigabytes_are_addressed_correctly():
     got = binding.deft_tree_attn_decode(plan, Q.cuda(), k, v, out_dtype=torch.float32)
     torch.cuda.synchronize()
     check(got.cpu().numpy().astype(np.float64), ref, strict=False)
+
+
+def test_decode_calls_captured_in_a_hip_graph_replay_to_the_eager_result():
+    """A decode call only enqueues two kernels on the caller's stream, so a layer loop can be captured once and
+    replayed.  Several replays, with eager work and synchronisations between them and fresh inputs written into
+    the captured buffers, each give exactly what the eager call gives."""
+    t = wl.random_tree(21, n_nodes=14, max_len=300, nq=11, Hq=8, Hkv=4, d=128)
+    L = 3
+    plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, 128)
+    g = torch.Generator().manual_seed(5)
+
+    def fresh():
+        return [torch.randn((t.nq, t.Hq, t.d), generator=g).to(torch.bfloat16).cuda() for _ in range(L)], \
+               [torch.randn((t.ntok, t.Hkv, t.d), generator=g).to(torch.bfloat16).cuda() for _ in range(L)], \
+               [torch.randn((t.ntok, t.Hkv, t.d), generator=g).to(torch.bfloat16).cuda() for _ in range(L)]
+
+    qs, ks, vs = fresh()
+    outs = [torch.empty((t.nq, t.Hq, t.d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+    ws = plan.workspace(t.Hq, t.Hkv, t.d, "cuda")
+    # eager warm-up: uploads the image and sets the kernel's LDS limit, neither of which belongs in a graph
+    for i in range(L):
+        binding.deft_tree_attn_decode(plan, qs[i], ks[i], vs[i], out=outs[i], workspace=ws)
+    torch.cuda.synchronize()
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(L):
+            binding.deft_tree_attn_decode(plan, qs[i], ks[i], vs[i], out=outs[i], workspace=ws)
+    for rep in range(4):
+        nq_, nk, nv = fresh()
+        for i in range(L):
+            qs[i].copy_(nq_[i])
+            ks[i].copy_(nk[i])
+            vs[i].copy_(nv[i])
+        for o in outs:
+            o.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [o.clone() for o in outs]
+        want = [binding.deft_tree_attn_decode(plan, qs[i], ks[i], vs[i]) for i in range(L)]
+        torch.cuda.synchronize()
+        for i in range(L):
+            assert torch.equal(got[i], want[i]), (rep, i)
+    ref = oracle.tree_attention(qs[0].cpu(), ks[0].cpu(), vs[0].cpu(), t.node_tok_begin, t.node_tok_len, t.node_parent,
+                                t.query_node)
+    check(got[0].float().cpu().numpy().astype(np.float64), ref, strict=False)
