@@ -1,6 +1,6 @@
 // Device side of libdeft: the Attention Calculation Phase of DeFT-Flatten (Algorithm 4) for gfx950.
 //
-// Stage 1 (deft_stage1): one workgroup of four waves per task = (chunk, KV head, up to four 16-row
+// Stage 1 (deft_stage1): one workgroup of four waves per task = (chunk, KV head, up to eight 16-row
 // tiles).  The rows of a tile are (query of the chunk's group) x (query head reading this KV head).
 // A wave streams 32 tokens at a time straight from HBM into MFMA operand registers:
 //
@@ -15,8 +15,8 @@
 // Each token row of one head (2*d bytes, contiguous) is fetched from HBM exactly once per task and every
 // byte of every 64-byte sector requested is used.  A narrow group (one row tile) splits the chunk's
 // tokens over the four waves, each keeping two blocks of loads in flight in registers.  A wider group
-// gives each wave its own row tile; the waves that need the same block each fetch a share of it and pass
-// the operand registers to the others through LDS.  The waves' partial results are merged in LDS before
+// gives each wave its own row tile (two tiles for tasks of more than four); the waves that need the same
+// block each fetch a share of it and pass the operand registers to the others through LDS.  The waves' partial results are merged in LDS before
 // one (m, l, acc) triple per (chunk, row) is written.
 //
 // Stage 2 (deft_stage2): one wave per (query, query head) merges that query's partial results with
