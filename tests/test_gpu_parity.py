@@ -4,7 +4,12 @@ Tolerance (bf16 inputs, fp32 accumulation, bf16 probabilities in the P.V product
   * the five benchmark configurations: max |err| <= 2e-3 over all elements AND, per (query, head)
     row, ||err||_2 / ||ref||_2 <= 1e-2;
   * arbitrary small trees, whose short paths give outputs of magnitude O(1) where one bf16 ulp
-    already exceeds 2e-3: element-wise |err| <= 2e-3 + 1e-2 |ref| and the same row-relative bound.
+    already exceeds 2e-3: the bound that follows from the arithmetic.  With u = 2^-8 the unit
+    roundoff of bf16, every softmax weight enters the P.V product with a relative error of at
+    most u and the denominator is the sum of the same rounded weights, so a normalised weight is
+    off by at most 2u of itself and an output element by at most 2u * sum_t w_t |V[t, c]|; the
+    bf16 output adds u |ref|.  sum_t w_t |V[t, c]| is the oracle's attention over |V|.
+    Element-wise |err| <= 2u * attention(|V|) + u |ref| + 1e-5, and the same row-relative bound.
 """
 
 import numpy as np
@@ -18,6 +23,7 @@ from paper_2404_00242_amd import binding, workloads as wl
 pytestmark = pytest.mark.gpu
 
 ABS_TOL, REL_TOL = 2e-3, 1e-2
+U_BF16 = 2.0 ** -8
 
 
 def run_gpu(t, Q, K, V, chunk_size=0, out_dtype=torch.bfloat16, scale=0.0, mode="flatten"):
@@ -34,6 +40,12 @@ def reference(t, Q, K, V, scale=None):
     return oracle.tree_attention(Q, K, V, t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, scale=scale)
 
 
+def reference_abs_v(t, Q, K, V, scale=None):
+    """sum_t w_t |V[t, c]|: what the rounding of the weights is multiplied by (see the module docstring)"""
+    return oracle.tree_attention(Q, K, V.abs(), t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node,
+                                 scale=scale)
+
+
 def errors(got, ref):
     err = np.abs(got - ref)
     num = np.sqrt(((got - ref) ** 2).sum(-1))
@@ -42,14 +54,15 @@ def errors(got, ref):
     return err, rel
 
 
-def check(got, ref, strict):
+def check(got, ref, strict, abs_v=None):
+    """strict: the benchmark configurations' bound; otherwise abs_v = reference_abs_v(...) gives the bound"""
     assert np.isfinite(got).all()
     err, rel = errors(got, ref)
     print(f"    max|err|={err.max():.3e} max row-rel={rel.max():.3e} max|ref|={np.abs(ref).max():.3f}", flush=True)
     if strict:
         assert err.max() <= ABS_TOL
     else:
-        assert (err <= ABS_TOL + REL_TOL * np.abs(ref)).all()
+        assert (err <= 2 * U_BF16 * abs_v + U_BF16 * np.abs(ref) + 1e-5).all()
     assert rel.max() <= REL_TOL
 
 
@@ -117,7 +130,7 @@ def test_stage1_partials_match_algorithm4_and_stage2_completes_them():
                                           ws.data_ptr(), ws.numel(), st)
     assert rc == 0
     torch.cuda.synchronize()
-    check(o.cpu().numpy().astype(np.float64), reference(t, Q, K, V), strict=False)
+    check(o.cpu().numpy().astype(np.float64), reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V))
 
 
 @pytest.mark.parametrize("mode", ["node", "node_chunk", "query"])
@@ -134,7 +147,7 @@ def test_other_partitioning_strategies_give_the_same_attention(mode):
                            n_roots=1 + seed % 2)
         Q, K, V = wl.make_qkv(t)
         got, _ = run_gpu(t, Q, K, V, chunk_size=64, out_dtype=torch.float32, mode=mode)
-        check(got, reference(t, Q, K, V), strict=False)
+        check(got, reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V))
 
 
 def test_tiny_variant_with_320_tokens():
@@ -164,12 +177,12 @@ def test_random_forests(seed):
                        Hq=Hq, Hkv=Hkv, d=d, n_roots=1 + seed % 3)
     print(f"\n  seed {seed}: nodes={t.n_nodes} ntok={t.ntok} nq={t.nq} Hq={Hq} Hkv={Hkv} d={d}", flush=True)
     Q, K, V = wl.make_qkv(t)
-    ref = reference(t, Q, K, V)
+    ref, abs_v = reference(t, Q, K, V), reference_abs_v(t, Q, K, V)
     for chunk in (32, 128):
         got, _ = run_gpu(t, Q, K, V, chunk_size=chunk, out_dtype=torch.float32)
-        check(got, ref, strict=False)
+        check(got, ref, strict=False, abs_v=abs_v)
     got, _ = run_gpu(t, Q, K, V, chunk_size=64)
-    check(got, ref, strict=False)
+    check(got, ref, strict=False, abs_v=abs_v)
 
 
 def test_wide_groups_and_many_row_tiles():
@@ -177,20 +190,20 @@ def test_wide_groups_and_many_row_tiles():
     t = wl._finish("star", [300] + [5] * 150, [-1] + [0] * 150, list(range(1, 151)), 8, 2, 128, 77)
     Q, K, V = wl.make_qkv(t)
     got, _ = run_gpu(t, Q, K, V, out_dtype=torch.float32)
-    check(got, reference(t, Q, K, V), strict=False)
+    check(got, reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V))
 
 
 def test_explicit_scale_and_empty_paths():
     t = wl.random_tree(3, n_nodes=6, max_len=50, nq=5, Hq=4, Hkv=2, d=128)
     Q, K, V = wl.make_qkv(t)
     got, _ = run_gpu(t, Q, K, V, out_dtype=torch.float32, scale=0.31)
-    check(got, reference(t, Q, K, V, scale=0.31), strict=False)
+    check(got, reference(t, Q, K, V, scale=0.31), strict=False, abs_v=reference_abs_v(t, Q, K, V, scale=0.31))
     # queries whose path has no token: zeros, and no kernel reads K/V
     t2 = wl._finish("empty", [0, 0, 7], [-1, 0, -1], [1, 1, 2], 4, 2, 64, 5, begins=[0, 0, 0], ntok=7)
     Q, K, V = wl.make_qkv(t2)
     got, _ = run_gpu(t2, Q, K, V, out_dtype=torch.float32)
     assert np.all(got[:2] == 0)
-    check(got, reference(t2, Q, K, V), strict=False)
+    check(got, reference(t2, Q, K, V), strict=False, abs_v=reference_abs_v(t2, Q, K, V))
     # no queries at all
     t3 = wl._finish("noq", [9], [-1], [], 4, 2, 64, 5)
     Q, K, V = wl.make_qkv(t3)
@@ -294,7 +307,7 @@ def test_head_counts_that_do_not_divide_the_dispatch_round(Hq, Hkv, d):
     Q, K, V = wl.make_qkv(t)
     got, plan = run_gpu(t, Q, K, V, chunk_size=32, out_dtype=torch.float32)
     assert plan.view()["n_chunks"] * Hkv > 512
-    check(got, reference(t, Q, K, V), strict=False)
+    check(got, reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V))
 
 
 def test_rows_beyond_four_gigabytes_are_addressed_correctly():
@@ -308,7 +321,7 @@ def test_rows_beyond_four_gigabytes_are_addressed_correctly():
     qn = [2, 1, 2]
     compact = wl._finish("compact", lens, parents, qn, Hq, Hkv, d, 123)
     Q, K, V = wl.make_qkv(compact)
-    ref = reference(compact, Q, K, V)
+    ref, abs_v = reference(compact, Q, K, V), reference_abs_v(compact, Q, K, V)
     k = torch.empty((n_rows, Hkv, d), dtype=torch.bfloat16, device="cuda")
     v = torch.empty((n_rows, Hkv, d), dtype=torch.bfloat16, device="cuda")
     for u in range(3):
@@ -318,7 +331,7 @@ def test_rows_beyond_four_gigabytes_are_addressed_correctly():
     plan = binding.deft_plan(begins_far, lens, parents, qn, n_rows, 64)
     got = binding.deft_tree_attn_decode(plan, Q.cuda(), k, v, out_dtype=torch.float32)
     torch.cuda.synchronize()
-    check(got.cpu().numpy().astype(np.float64), ref, strict=False)
+    check(got.cpu().numpy().astype(np.float64), ref, strict=False, abs_v=abs_v)
 
 
 def test_decode_calls_captured_in_a_hip_graph_replay_to_the_eager_result():
@@ -363,6 +376,6 @@ def test_decode_calls_captured_in_a_hip_graph_replay_to_the_eager_result():
         torch.cuda.synchronize()
         for i in range(L):
             assert torch.equal(got[i], want[i]), (rep, i)
-    ref = oracle.tree_attention(qs[0].cpu(), ks[0].cpu(), vs[0].cpu(), t.node_tok_begin, t.node_tok_len, t.node_parent,
-                                t.query_node)
-    check(got[0].float().cpu().numpy().astype(np.float64), ref, strict=False)
+    ref = reference(t, qs[0].cpu(), ks[0].cpu(), vs[0].cpu())
+    abs_v = reference_abs_v(t, qs[0].cpu(), ks[0].cpu(), vs[0].cpu())
+    check(got[0].float().cpu().numpy().astype(np.float64), ref, strict=False, abs_v=abs_v)
