@@ -379,3 +379,44 @@ def test_decode_calls_captured_in_a_hip_graph_replay_to_the_eager_result():
     ref = reference(t, qs[0].cpu(), ks[0].cpu(), vs[0].cpu())
     abs_v = reference_abs_v(t, qs[0].cpu(), ks[0].cpu(), vs[0].cpu())
     check(got[0].float().cpu().numpy().astype(np.float64), ref, strict=False, abs_v=abs_v)
+
+
+def test_randomised_sweep_of_shapes_strategies_and_storage():
+    """120 random trees; head counts, head dimension, chunk size, partitioning strategy and storage form
+    (contiguous / paged) drawn independently for each, a quarter of them with long nodes and wide groups."""
+    rng = np.random.default_rng(2024)
+    modes = list(binding.SPLIT_MODES)
+    worst = 0.0
+    for it in range(120):
+        Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+        G = int(rng.choice([1, 2, 4, 5, 8]))
+        d = int(rng.choice([64, 128]))
+        seed = int(rng.integers(1 << 30))
+        big = rng.random() < 0.25
+        t = wl.random_tree(seed, n_nodes=int(rng.integers(1, 40)), max_len=int(rng.integers(1, 2500 if big else 400)),
+                           nq=int(rng.integers(1, 300 if big else 80)), Hq=Hkv * G, Hkv=Hkv, d=d,
+                           n_roots=int(rng.integers(1, 4)), zero_len_prob=float(rng.choice([0, 0.1, 0.3])))
+        Q, K, V = wl.make_qkv(t)
+        chunk = int(rng.choice([32, 64, 96, 128, 256, 512, 1024, 4096]))
+        mode = modes[int(rng.integers(len(modes)))]
+        page = int(rng.choice([1, 4, 16, 64])) if rng.random() < 0.3 else 0
+        case = f"case {it}: seed={seed} Hkv={Hkv} G={G} d={d} chunk={chunk} mode={mode} page={page} nodes={t.n_nodes} nq={t.nq}"
+        ref, abs_v = reference(t, Q, K, V), reference_abs_v(t, Q, K, V)
+        if page:
+            pp, pg, npool, row_of = wl.to_paged(t, page, seed=seed)
+            kp = wl.scatter_to_pool(K, row_of, npool * page, 1).cuda()
+            vp = wl.scatter_to_pool(V, row_of, npool * page, 2).cuda()
+            plan = binding.deft_plan_paged(pp, pg, page, npool, t.node_tok_len, t.node_parent, t.query_node, chunk,
+                                           binding.SPLIT_MODES[mode])
+            got = binding.deft_tree_attn_decode(plan, Q.cuda(), kp, vp, out_dtype=torch.float32)
+        else:
+            plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, chunk,
+                                     binding.SPLIT_MODES[mode])
+            got = binding.deft_tree_attn_decode(plan, Q.cuda(), K.cuda(), V.cuda(), out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        got = got.cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all(), case
+        frac = np.abs(got - ref) / (2 * U_BF16 * abs_v + 1e-5)
+        worst = max(worst, float(frac.max()))
+        assert frac.max() <= 1.0, case
+    print(f"\n    120 cases, largest error as a fraction of the bound: {worst:.3f}", flush=True)
