@@ -48,9 +48,6 @@ struct Stage1Args {
     int32_t n_items, Hq, Hkv, G;
     int32_t table_len;  // entries of the LDS per-token table: longest multi-piece chunk, in whole blocks
     float c;  // scale * log2(e): probabilities are 2^((s - m) * c)
-#ifdef DEFT_TRACE
-    unsigned long long *trace;  // developer build only: 4 timestamps per wave
-#endif
 };
 
 struct Stage2Args {
@@ -421,9 +418,6 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     int32_t *s_qlo = s_row + a.table_len;
     int32_t *s_qhi = s_qlo + a.table_len;
 
-#ifdef DEFT_TRACE
-    const unsigned long long t_begin = wall_clock64();
-#endif
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the block loops on scalar branches
@@ -533,9 +527,6 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     const float lazy = kLazyLog2 / a.c;
     TileState<D>(&ts1)[1] = reinterpret_cast<TileState<D>(&)[1]>(ts);  // the one-tile paths use ts[0] only
 
-#ifdef DEFT_TRACE
-    const unsigned long long t_pro = wall_clock64();
-#endif
     if (TR == 1) {
         SplitPipe<D> pipe;
         pipe.prime(ctx, wave, nblk);
@@ -558,9 +549,6 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
         pipe.run(ctx, xbuf, wave, lane, nblk, ts, a.c, lazy);
     }
 
-#ifdef DEFT_TRACE
-    const unsigned long long t_loop = wall_clock64();
-#endif
     // ---- merge the token parts in LDS and write one partial result per (chunk, row):
     //      m = reference maximum of the raw scores, l = sum of exp, acc = un-normalised weighted values.
     //      One round per tile of the wave; the exchange buffer is dead by now and the merge buffer takes its place.
@@ -628,19 +616,6 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
                 *reinterpret_cast<f32x4 *>(dst + e) = f32x4{o[e], o[e + 1], o[e + 2], o[e + 3]};
         }
     }
-#ifdef DEFT_TRACE
-    if (a.trace && lane == 0) {
-        unsigned long long *t = a.trace + ((size_t)blockIdx.x * kWaves + wave) * 4;
-        t[0] = t_begin;
-        t[1] = t_pro;
-        t[2] = t_loop;
-        // low 40 bits: end time; high bits: HW_ID (reg 4) and XCC_ID (reg 20) for placement studies
-        const unsigned hw = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));
-        const unsigned xcc = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (3 << 11));
-        t[3] = (wall_clock64() & 0xffffffffffull) | ((unsigned long long)(hw & 0xffff) << 40) |
-               ((unsigned long long)(xcc & 0xf) << 56);
-    }
-#endif
 }
 
 // Stage 2: tree-topology-aware global reduction (eq. 1 with the largest maximum subtracted).
@@ -858,12 +833,6 @@ int run_stage1(const deft_plan_t *plan, const Call &call, const void *q, const v
     a1.G = Hq / Hkv;
     a1.table_len = S.table_len;
     a1.c = call.c;
-#ifdef DEFT_TRACE
-    {
-        const char *e = getenv("DEFT_TRACE_BUF");
-        a1.trace = e ? reinterpret_cast<unsigned long long *>(strtoull(e, nullptr, 0)) : nullptr;
-    }
-#endif
     const bool ok = d == 128 ? launch_stage1<128>(S, a1, call.img, call.stream)
                              : launch_stage1<64>(S, a1, call.img, call.stream);
     return ok ? DEFT_OK : DEFT_EHIP;
