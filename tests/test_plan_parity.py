@@ -153,3 +153,49 @@ def test_other_partitioning_strategies(mode):
         assert_same_plan(wl.make_config(cfg), 128, mode)
     with pytest.raises(binding.DeftError):
         binding.deft_plan([0], [4], [-1], [0], 4, 32, 7)       # unknown strategy
+
+
+def test_corrupted_trees_are_accepted_or_refused_exactly_as_by_the_oracle():
+    """400 valid random forests with one to three random corruptions each (parent, length, position, query,
+    chunk size, cache size): the planner returns an error exactly when the oracle's validation raises, and when
+    both accept, the plans are equal."""
+    rng = np.random.default_rng(77)
+    refused = accepted = 0
+    for it in range(400):
+        t = wl.random_tree(9000 + it, n_nodes=int(rng.integers(1, 12)), max_len=int(rng.integers(1, 50)),
+                           nq=int(rng.integers(0, 9)), n_roots=int(rng.integers(1, 3)))
+        nb, nl, par, qn = (np.array(x, dtype=np.int64) for x in
+                           (t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node))
+        ntok, chunk = int(t.ntok), 32
+        for _ in range(int(rng.integers(1, 4))):
+            kind = int(rng.integers(6))
+            u = int(rng.integers(len(nb)))
+            if kind == 0:
+                par[u] = int(rng.integers(-3, len(nb) + 2))
+            elif kind == 1:
+                nl[u] = int(rng.integers(-2, 80))
+            elif kind == 2:
+                nb[u] = int(rng.integers(-2, ntok + 5))
+            elif kind == 3 and len(qn):
+                qn[int(rng.integers(len(qn)))] = int(rng.integers(-2, len(nb) + 2))
+            elif kind == 4:
+                chunk = int(rng.choice([0, -32, 16, 48, 64, 4096]))  # the 4096 cap is the kernels', tested above
+            else:
+                ntok = int(rng.integers(-1, ntok + 3))
+        try:
+            want = flatten_plan(nb, nl, par, qn, ntok, chunk if chunk else 128)
+        except PlanError:
+            want = None
+        try:
+            got = binding.deft_plan(nb.astype(np.int32), nl.astype(np.int32), par.astype(np.int32),
+                                    qn.astype(np.int32), ntok, chunk).view()
+        except binding.DeftError:
+            got = None
+        assert (want is None) == (got is None), (it, nb, nl, par, qn, ntok, chunk)
+        if want is None:
+            refused += 1
+        else:
+            accepted += 1
+            for key in ("seg_tok_begin", "seg_len", "seg_qlo", "seg_qhi", "chunk_qlo", "chunk_qhi", "q_part_slot", "q_order"):
+                assert np.array_equal(got[key], want[key]), (it, key)
+    assert refused > 100 and accepted > 50
