@@ -41,6 +41,21 @@ def test_library_exports_every_declared_symbol(repo_root):
     assert lib.deft_strerror(0) == b"ok" and lib.deft_strerror(-3) != lib.deft_strerror(-1)
 
 
+def test_public_header_is_plain_c(repo_root, tmp_path):
+    """The boundary is a C ABI: its header must compile as C99 (and as C++) with nothing but itself."""
+    import shutil
+    import subprocess
+
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "deft.h"\nint main(void) { deft_plan_view_t v; (void)v; return DEFT_OK; }\n')
+    inc = os.path.join(repo_root, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(src)],
+                   check=True)
+    if shutil.which("g++"):
+        subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c++",
+                        "-I", inc, str(src)], check=True)
+
+
 @pytest.mark.parametrize("cfg,B", [(1, 128), (1, 32), (2, 128), (2, 256), (3, 128), (3, 32), (4, 128), (5, 128),
                                    (5, 1024)])
 def test_benchmark_configs(cfg, B):
