@@ -170,6 +170,8 @@ def main():
             raise RuntimeError(f"{what} failed: {lib.deft_strerror(rc).decode()} {lib.deft_last_hip_error().decode()}")
 
     def prepare():
+        # deft_plan_upload waits for the stream, i.e. for the previous step's kernels: in a decode loop the next
+        # tree depends on that step's output, so the preparation phase is on the critical path here as well
         h = vp()
         if lib.deft_suggest_chunk_size(nlp, parp, tree.n_nodes, qnp, tree.nq, Hq, Hkv) < 0:
             raise RuntimeError("deft_suggest_chunk_size failed")

@@ -154,10 +154,12 @@ int deft_plan_paged(const int32_t *node_page_ptr, const int32_t *page_ids, int32
 
 /*
  * A chunk size S_t suited to this tree on an MI355X (the paper leaves S_t as a tuning knob, Fig. 11):
- * the multiple of 128 in [128, 1024] that makes the number of stage-1 tasks, (chunk, KV head, 128 rows of
- * the chunk's query group), about twice the number of compute units, so that every unit streams the
- * same number of KV bytes.  Host arrays as for deft_plan (token begins are not needed).  Returns the
- * size, or a negative deft_status on malformed input.  Any valid S_t gives the same attention result.
+ * the multiple of 128 that makes the number of stage-1 tasks, (chunk, KV head, 128 rows of the chunk's
+ * query group), about twice the number of compute units, so that every unit streams the same number of
+ * KV bytes; at least 128 and at most 768, or at most 1024 when some group is wider than one task (fewer
+ * partial results).  A heuristic from measurements, not an optimum.  Host arrays as for deft_plan (token
+ * begins are not needed).  Returns the size, or a negative deft_status on malformed input.  Any valid
+ * S_t gives the same attention result.
  */
 int32_t deft_suggest_chunk_size(const int32_t *node_tok_len, const int32_t *node_parent, int32_t n_nodes,
                                 const int32_t *query_node, int32_t nq, int32_t Hq, int32_t Hkv);
