@@ -170,8 +170,9 @@ def main():
             raise RuntimeError(f"{what} failed: {lib.deft_strerror(rc).decode()} {lib.deft_last_hip_error().decode()}")
 
     def prepare():
-        # deft_plan_upload waits for the stream, i.e. for the previous step's kernels: in a decode loop the next
-        # tree depends on that step's output, so the preparation phase is on the critical path here as well
+        # the upload is only enqueued (pinned staging inside the library), so the host prepares the next step
+        # while the GPU still runs this one; the copy is ordered behind this step's kernels on the stream, which
+        # is what makes reusing the one image buffer safe
         h = vp()
         if lib.deft_suggest_chunk_size(nlp, parp, tree.n_nodes, qnp, tree.nq, Hq, Hkv) < 0:
             raise RuntimeError("deft_suggest_chunk_size failed")

@@ -12,7 +12,8 @@
  * Conventions
  *   - All functions return 0 (DEFT_OK) or a negative deft_status; nothing throws.
  *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
- *     memory on the current device.  The library allocates no device memory:
+ *     memory on the current device.  The library allocates no device memory (only, at
+ *     the first deft_plan_upload on a device, 2 MiB of pinned host memory for staging):
  *     Q/K/V/O, the plan's device image and the workspace all belong to the caller.
  *   - deft_tree_attn_decode only enqueues kernels on the given stream; it does not
  *     synchronise.  Calls that share a workspace must be ordered by the caller.
@@ -173,9 +174,11 @@ int deft_plan_view(const deft_plan_t *plan, deft_plan_view_t *out);
  * rows "query x query-head of one KV head" of each chunk's group are tiled over waves).
  * deft_plan_device_bytes returns the size the caller must provide (0 on bad arguments);
  * deft_plan_upload packs the image on the host and copies it into dev_image (device
- * memory, 16-byte aligned) on `stream` (a hipStream_t, NULL = default stream), waiting
- * for the copy to finish before returning.  One image serves one Hq/Hkv ratio; a plan
- * may be uploaded for several.
+ * memory, 16-byte aligned) on `stream` (a hipStream_t, NULL = default stream).  Images of
+ * up to 256 KiB are staged in pinned host memory that the library keeps per device, and the
+ * call only enqueues the copy: work enqueued on `stream` afterwards sees the image, and the
+ * plan may be destroyed at once.  Larger images are copied from the plan and the call waits
+ * for that copy.  One image serves one Hq/Hkv ratio; a plan may be uploaded for several.
  * Errors: DEFT_EINVAL (null, Hq <= 0, Hkv <= 0, Hq % Hkv != 0), DEFT_EWORKSPACE (bytes
  * too small), DEFT_EHIP.
  */

@@ -28,6 +28,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 
 #include "deft_internal.h"
@@ -862,6 +863,53 @@ int run_stage2(const deft_plan_t *plan, const Call &call, void *o, int32_t Hq, i
     return ok ? DEFT_OK : DEFT_EHIP;
 }
 
+// Pinned host staging for plan images: a ring of slots per device, allocated at the first upload on that
+// device and kept until the process ends.  An image is copied into the next slot and sent from there with
+// an asynchronous copy, so deft_plan_upload neither waits for the stream nor depends on the plan staying
+// alive.  A slot is reused only after the event recorded behind its last copy has completed.
+constexpr int kStageSlots = 8;
+constexpr size_t kStageSlotBytes = 256 * 1024;
+struct Staging {
+    std::mutex mu;
+    uint8_t *base = nullptr;
+    hipEvent_t done[kStageSlots] = {};
+    bool used[kStageSlots] = {};
+    int next = 0;
+};
+Staging g_staging[64];
+
+// Returns 1 when the image went out through the ring, 0 when the caller has to take the plain path
+// (image larger than a slot, device index out of range), -1 on a runtime error.
+int upload_staged(void *dev_image, const uint8_t *src, size_t bytes, hipStream_t st) {
+    int dev = 0;
+    if (bytes > kStageSlotBytes) return 0;
+    if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return -1;
+    if (dev < 0 || dev >= 64) return 0;
+    Staging &g = g_staging[dev];
+    std::lock_guard<std::mutex> lock(g.mu);
+    if (!g.base) {
+        void *p = nullptr;
+        if (!hip_ok(hipHostMalloc(&p, kStageSlots * kStageSlotBytes, hipHostMallocDefault), "pinned staging")) return -1;
+        for (int i = 0; i < kStageSlots; ++i) {
+            if (!hip_ok(hipEventCreateWithFlags(&g.done[i], hipEventDisableTiming), "staging event")) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(g.done[j]);
+                (void)hipHostFree(p);
+                return -1;
+            }
+        }
+        g.base = static_cast<uint8_t *>(p);
+    }
+    const int i = g.next;
+    g.next = (g.next + 1) % kStageSlots;
+    if (g.used[i] && !hip_ok(hipEventSynchronize(g.done[i]), "staging slot")) return -1;
+    uint8_t *slot = g.base + (size_t)i * kStageSlotBytes;
+    std::memcpy(slot, src, bytes);
+    if (!hip_ok(hipMemcpyAsync(dev_image, slot, bytes, hipMemcpyHostToDevice, st), "plan upload")) return -1;
+    if (!hip_ok(hipEventRecord(g.done[i], st), "staging event record")) return -1;
+    g.used[i] = true;
+    return 1;
+}
+
 }  // namespace
 
 extern "C" const char *deft_last_hip_error(void) { return g_hip_error.c_str(); }
@@ -885,6 +933,10 @@ extern "C" int deft_plan_upload(deft_plan_t *plan, int32_t Hq, int32_t Hkv, void
     }
     if (bytes < S->bytes) return DEFT_EWORKSPACE;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const int staged = upload_staged(dev_image, S->host_image.data(), S->bytes, st);
+    if (staged < 0) return DEFT_EHIP;
+    if (staged > 0) return DEFT_OK;
+    // an image larger than a staging slot goes from the plan's own (pageable) copy, and the call waits for it
     if (!hip_ok(hipMemcpyAsync(dev_image, S->host_image.data(), S->bytes, hipMemcpyHostToDevice, st), "plan upload"))
         return DEFT_EHIP;
     if (!hip_ok(hipStreamSynchronize(st), "plan upload sync")) return DEFT_EHIP;

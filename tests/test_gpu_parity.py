@@ -420,3 +420,29 @@ def test_randomised_sweep_of_shapes_strategies_and_storage():
         worst = max(worst, float(frac.max()))
         assert frac.max() <= 1.0, case
     print(f"\n    120 cases, largest error as a fraction of the bound: {worst:.3f}", flush=True)
+
+
+def test_uploads_are_only_enqueued_and_may_outrun_the_stream():
+    """Twenty plans are uploaded and used back to back without any synchronisation (more than the library's
+    eight pinned staging slots, so slots are reused while earlier copies may still be queued), and every
+    plan object is dropped as soon as its calls are enqueued; then one synchronisation, and every result is
+    checked."""
+    dev = torch.device("cuda:0")
+    cases = []
+    for seed in range(20):
+        t = wl.random_tree(300 + seed, n_nodes=4 + seed % 9, max_len=200, nq=2 + seed % 11, Hq=8, Hkv=2, d=128)
+        Q, K, V = wl.make_qkv(t)
+        cases.append((t, Q, K, V, Q.to(dev), K.to(dev), V.to(dev)))
+    # something long on the stream first, so that the uploads really queue up behind it
+    big = torch.empty(1 << 28, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    for _ in range(4):
+        big.add_(1)
+    outs = []
+    for (t, Q, K, V, q, k, v) in cases:
+        plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, 64)
+        outs.append(binding.deft_tree_attn_decode(plan, q, k, v, out_dtype=torch.float32))
+        del plan
+    torch.cuda.synchronize()
+    for (t, Q, K, V, *_), o in zip(cases, outs):
+        check(o.cpu().numpy().astype(np.float64), reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V))
