@@ -57,6 +57,14 @@ typedef enum deft_status {
 #define DEFT_SPLIT_NODE 1u
 #define DEFT_SPLIT_NODE_CHUNK 2u
 #define DEFT_GROUP_QUERY 3u
+/*
+ * May be or-ed to any of the above.  Stage 1 rounds the softmax weights to bf16 for its matrix products
+ * (fp32 sums); a weight then carries a relative error of up to 2^-8.  Over a long path these errors average
+ * out; a group one of whose queries has fewer than 1024 tokens on its whole path is therefore always
+ * computed with two-term weights (hi + lo bf16, relative error 2^-17).  This flag asks for two-term weights
+ * in every group, whatever the path lengths, at the price of half again as many matrix instructions.
+ */
+#define DEFT_PRECISE_WEIGHTS 0x100u
 
 #define DEFT_DEFAULT_CHUNK 128 /* the paper's default KV block size (chunk-size ablation, Fig. 11) */
 #define DEFT_MAX_CHUNK 4096
@@ -122,7 +130,8 @@ typedef struct deft_plan_view {
  *     may share a node and may sit on inner nodes.
  * chunk_size : S_t, tokens per chunk; 0 selects DEFT_DEFAULT_CHUNK; otherwise a positive
  *     multiple of 32, at most DEFT_MAX_CHUNK.
- * flags      : DEFT_SPLIT_FLATTEN (0, the paper's method) or one of the comparison strategies above.
+ * flags      : DEFT_SPLIT_FLATTEN (0, the paper's method) or one of the comparison strategies above,
+ *     optionally or-ed with DEFT_PRECISE_WEIGHTS.
  * out_plan   : receives a host object owned by the library; release with deft_plan_destroy.
  *     The plan is immutable, depends on the tree only, and can be reused for every layer
  *     and every call that sees the same tree.
@@ -204,7 +213,7 @@ size_t deft_workspace_bytes(const deft_plan_t *plan, int32_t Hq, int32_t Hkv, in
  *             K pool starts on one, so that the K and V rows of a head differ in address
  *             bits 7..9; the Python binding's alloc_kv_cache does that.  Optional.)
  * o         : device [nq, Hq, d], bf16 (DEFT_OUT_BF16) or float (DEFT_OUT_F32), caller's
- *             query order.  A query whose path holds no token gets zeros.
+ *             query order, 16-byte aligned.  A query whose path holds no token gets zeros.
  * d         : 64 or 128.  Hq % Hkv == 0.
  * scale     : softmax scale; <= 0 selects 1/sqrt(d).
  * workspace : device memory of at least deft_workspace_bytes(plan, Hq, Hkv, d), 16-byte

@@ -24,6 +24,7 @@ DEFT_SPLIT_FLATTEN = 0
 DEFT_SPLIT_NODE = 1
 DEFT_SPLIT_NODE_CHUNK = 2
 DEFT_GROUP_QUERY = 3
+DEFT_PRECISE_WEIGHTS = 0x100  # or-ed to a mode: two-term softmax weights in every group
 SPLIT_MODES = {"flatten": DEFT_SPLIT_FLATTEN, "node": DEFT_SPLIT_NODE, "node_chunk": DEFT_SPLIT_NODE_CHUNK,
                "query": DEFT_GROUP_QUERY}
 

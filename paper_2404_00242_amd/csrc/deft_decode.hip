@@ -165,7 +165,14 @@ struct TileState {
 
 // Online-softmax step of one wave over one 32-token block, for its NT row tiles.  The K and V operands are
 // shared by the tiles, so the loads (or LDS reads) and the V interleave are paid once per block.
-template <int D, int NT>
+//
+// PRECISE: every weight enters the P.V product and the denominator as the sum of two bf16 numbers, hi =
+// bf16(p) and lo = bf16(p - hi), through a second set of MFMAs, so it carries a relative error of 2^-17
+// instead of bf16's 2^-9.  The plan asks for it where some query of the group has a short path: there a
+// handful of rounded weights does not average out and an output element would be off by up to
+// 2^-7 * sum_t w_t |V_t|.  The matrix pipe has the room (a bandwidth-bound block keeps it busy for a sixth
+// of its time).
+template <int D, int NT, bool PRECISE>
 __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx &c, int x0, TileState<D> (&ts)[NT],
                                               const float cs, const float lazy) {
     constexpr int KK = D / 32;
@@ -211,7 +218,7 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
         }
     }
 
-    bf16x8 preg[NT];
+    bf16x8 preg[NT], plo[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         RowState &st = ts[t].rs;
@@ -237,6 +244,17 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
         const u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]),
                           pack_bf16(pv[6], pv[7])};
         preg[t] = __builtin_bit_cast(bf16x8, pk);
+        if (PRECISE) {
+            // what the rounding to bf16 dropped, itself rounded to bf16 (hi widens to fp32 by a 16-bit shift)
+            u32x4 lk;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float h0 = __builtin_bit_cast(float, pk[j] << 16);
+                const float h1 = __builtin_bit_cast(float, pk[j] & 0xffff0000u);
+                lk[j] = pack_bf16(pv[2 * j] - h0, pv[2 * j + 1] - h1);
+            }
+            plo[t] = __builtin_bit_cast(bf16x8, lk);
+        }
     }
 
     // l += column sums of P^T
@@ -244,8 +262,10 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
         const u32x4 one4 = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // eight bf16 1.0
         const bf16x8 ones = __builtin_bit_cast(bf16x8, one4);
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+        for (int t = 0; t < NT; ++t) {
             ts[t].rs.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, preg[t], ts[t].rs.l, 0, 0, 0);
+            if (PRECISE) ts[t].rs.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, plo[t], ts[t].rs.l, 0, 0, 0);
+        }
     }
 
     // O^T += V^T P^T.  The V^T operand of product c' = 2*c2 + {0,1} is a 16-bit interleave of token pairs:
@@ -265,6 +285,12 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
                                                                        ts[t].o[2 * c2], 0, 0, 0);
             ts[t].o[2 * c2 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt_hi), preg[t],
                                                                            ts[t].o[2 * c2 + 1], 0, 0, 0);
+            if (PRECISE) {
+                ts[t].o[2 * c2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt_lo), plo[t],
+                                                                           ts[t].o[2 * c2], 0, 0, 0);
+                ts[t].o[2 * c2 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt_hi), plo[t],
+                                                                               ts[t].o[2 * c2 + 1], 0, 0, 0);
+            }
         }
     }
 }
@@ -278,12 +304,13 @@ struct SplitPipe {
         load_block<D>(b0, ctx, wave * 32, wave < nblk);
         load_block<D>(b1, ctx, (wave + kWaves) * 32, wave + kWaves < nblk);
     }
+    template <bool PRECISE>
     __device__ __forceinline__ void run(const ChunkCtx &ctx, int wave, int nblk, TileState<D> (&ts)[1], float cs,
                                         float lazy) {
         for (int blk = wave; blk < nblk; blk += 2 * kWaves) {
-            compute_block<D, 1>(b0, ctx, blk * 32, ts, cs, lazy);
+            compute_block<D, 1, PRECISE>(b0, ctx, blk * 32, ts, cs, lazy);
             load_block<D>(b0, ctx, (blk + 2 * kWaves) * 32, blk + 2 * kWaves < nblk);
-            if (blk + kWaves < nblk) compute_block<D, 1>(b1, ctx, (blk + kWaves) * 32, ts, cs, lazy);
+            if (blk + kWaves < nblk) compute_block<D, 1, PRECISE>(b1, ctx, (blk + kWaves) * 32, ts, cs, lazy);
             load_block<D>(b1, ctx, (blk + 3 * kWaves) * 32, blk + 3 * kWaves < nblk);
         }
     }
@@ -328,7 +355,7 @@ __device__ __forceinline__ void share_issue(Share<D, TR> &s, const ChunkCtx &c, 
     }
 }
 
-template <int D, int TR, int NT>
+template <int D, int TR, int NT, bool PRECISE>
 __device__ __forceinline__ void share_step(Share<D, TR> &s, const ChunkCtx &c, u32x4 *xs, int t, int lane, int blk,
                                            int next_blk, int nblk, TileState<D> (&ts)[NT], float cs, float lazy) {
     constexpr int KK = D / 32;
@@ -356,7 +383,7 @@ __device__ __forceinline__ void share_step(Share<D, TR> &s, const ChunkCtx &c, u
             for (int kk = 0; kk < KK; ++kk) r.k[aa][kk] = __builtin_bit_cast(bf16x8, xs[(aa * KK + kk) * 64 + lane]);
 #pragma unroll
         for (int j = 0; j < 8; ++j) r.v[j] = xs[(2 * KK + j) * 64 + lane];
-        compute_block<D, NT>(r, c, blk * 32, ts, cs, lazy);
+        compute_block<D, NT, PRECISE>(r, c, blk * 32, ts, cs, lazy);
     }
 }
 
@@ -377,6 +404,7 @@ struct SharedPipe {
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u) share_issue<D, TR>(st[u], ctx, t, (part + u * NP) * 32, part + u * NP < nblk);
     }
+    template <bool PRECISE>
     __device__ __forceinline__ void run(const ChunkCtx &ctx, u32x4 *xbuf, int wave, int lane, int nblk,
                                         TileState<D> (&ts)[NT], float cs, float lazy) {
         const int t = wave % TR, part = wave / TR;
@@ -390,7 +418,7 @@ struct SharedPipe {
                 const int blk = part + it * NP;
                 // LDS exchange stages alternate; stage (it & 1) was last read two steps ago, before the
                 // barrier of the previous step
-                share_step<D, TR, NT>(st[u], ctx, xb + (it & 1) * S::NSLOT * 64, t, lane, blk, blk + DEPTH * NP, nblk,
+                share_step<D, TR, NT, PRECISE>(st[u], ctx, xb + (it & 1) * S::NSLOT * 64, t, lane, blk, blk + DEPTH * NP, nblk,
                                       ts, cs, lazy);
             }
         }
@@ -403,7 +431,11 @@ struct SharedPipe {
 // remain: wave w works on tile w % TR and token part w / TR.  A task of 5-8 tiles gives every wave two
 // tiles.  The parts' partial results are merged in LDS, so one (m, l, acc) triple per (chunk, row)
 // reaches the workspace.
-template <int D>
+//
+// PRECISE selects two-term softmax weights (see compute_block).  The two variants are separate kernels so
+// that the extra registers of the precise one do not weigh on the other; a plan's tasks are listed by
+// variant and a call launches each non-empty list.
+template <int D, bool PRECISE>
 __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     constexpr int KK = D / 32;  // k-steps of the Q.K^T contraction
     // The P.V product runs as 8 MFMAs per block (a lane loads 8 d of V per token).  With D = 64 lanes
@@ -534,22 +566,22 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
         SplitPipe<D> pipe;
         pipe.prime(ctx, wave, nblk);
         load_q(1);
-        pipe.run(ctx, wave, nblk, ts1, a.c, lazy);
+        pipe.template run<PRECISE>(ctx, wave, nblk, ts1, a.c, lazy);
     } else if (TR == 2) {
         SharedPipe<D, 2, 1> pipe;
         pipe.prime(ctx, wave, nblk);
         load_q(1);
-        pipe.run(ctx, xbuf, wave, lane, nblk, ts1, a.c, lazy);
+        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts1, a.c, lazy);
     } else if (NTW == 1) {
         SharedPipe<D, 4, 1> pipe;
         pipe.prime(ctx, wave, nblk);
         load_q(1);
-        pipe.run(ctx, xbuf, wave, lane, nblk, ts1, a.c, lazy);
+        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts1, a.c, lazy);
     } else {
         SharedPipe<D, 4, 2> pipe;
         pipe.prime(ctx, wave, nblk);
         load_q(2);
-        pipe.run(ctx, xbuf, wave, lane, nblk, ts, a.c, lazy);
+        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts, a.c, lazy);
     }
 
     // ---- merge the token parts in LDS and write one partial result per (chunk, row):
@@ -749,28 +781,44 @@ bool hip_ok(hipError_t e, const char *what) {
     return false;
 }
 
+// The kernels may use more than the default 64 KB of dynamic LDS: the limit of both variants is raised once
+// per device, at the first call that launches either of them.
 template <int D>
-bool launch_stage1(const deft::Schedule &S, Stage1Args a1, const uint8_t *image, hipStream_t stream) {
-    a1.items = reinterpret_cast<const int32_t *>(image + S.off_items);
-    a1.n_items = S.n_items;
-    if (a1.n_items == 0) return true;
-    const size_t lds = kXbufBytes + 3 * (size_t)a1.table_len * sizeof(int32_t);
-    // the kernel may use more than the default 64 KB of dynamic LDS: raise the limit once per device
-    static std::atomic<uint64_t> configured[2];  // bit i set: done on device i, per head dimension
+bool configure_stage1() {
+    static std::atomic<uint64_t> configured;  // bit i set: done on device i (one flag per head dimension)
     int dev = 0;
     if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return false;
-    std::atomic<uint64_t> &mask = configured[D == 128];
-    if (dev < 0 || dev >= 64 || !((mask.load(std::memory_order_acquire) >> dev) & 1)) {
-        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void *>(&deft_stage1<D>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        kXbufBytes + 3 * DEFT_MAX_CHUNK * (int)sizeof(int32_t)),
-                    "deft_stage1 LDS size"))
-            return false;
-        if (dev >= 0 && dev < 64) mask.fetch_or(1ull << dev, std::memory_order_release);
-    }
-    const unsigned grid = (unsigned)a1.n_items * (unsigned)a1.Hkv;
-    hipLaunchKernelGGL((deft_stage1<D>), dim3(grid), dim3(64 * kWaves), lds, stream, a1);
+    if (dev >= 0 && dev < 64 && ((configured.load(std::memory_order_acquire) >> dev) & 1)) return true;
+    const int bytes = kXbufBytes + 3 * DEFT_MAX_CHUNK * (int)sizeof(int32_t);
+    if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void *>(&deft_stage1<D, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, bytes), "deft_stage1 LDS size") ||
+        !hip_ok(hipFuncSetAttribute(reinterpret_cast<const void *>(&deft_stage1<D, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, bytes), "deft_stage1 LDS size"))
+        return false;
+    if (dev >= 0 && dev < 64) configured.fetch_or(1ull << dev, std::memory_order_release);
+    return true;
+}
+
+template <int D, bool PRECISE>
+bool launch_stage1_variant(Stage1Args a1, const int32_t *items, int32_t n_items, hipStream_t stream) {
+    if (n_items == 0) return true;
+    a1.items = items;
+    a1.n_items = n_items;
+    const size_t lds = kXbufBytes + 3 * (size_t)a1.table_len * sizeof(int32_t);
+    const unsigned grid = (unsigned)n_items * (unsigned)a1.Hkv;
+    hipLaunchKernelGGL((deft_stage1<D, PRECISE>), dim3(grid), dim3(64 * kWaves), lds, stream, a1);
     return hip_ok(hipGetLastError(), "deft_stage1 launch");
+}
+
+// The task list holds the tasks with bf16 weights first, then those with two-term weights.
+template <int D>
+bool launch_stage1(const deft::Schedule &S, const Stage1Args &a1, const uint8_t *image, hipStream_t stream) {
+    if (S.n_items == 0) return true;
+    if (!configure_stage1<D>()) return false;
+    const int32_t *items = reinterpret_cast<const int32_t *>(image + S.off_items);
+    const int32_t n_fast = S.n_items - S.n_items_precise;
+    return launch_stage1_variant<D, false>(a1, items, n_fast, stream) &&
+           launch_stage1_variant<D, true>(a1, items + (size_t)n_fast * deft::kItemInts, S.n_items_precise, stream);
 }
 
 template <int D>
@@ -844,7 +892,7 @@ int run_stage1(const deft_plan_t *plan, const Call &call, const void *q, const v
 int run_stage2(const deft_plan_t *plan, const Call &call, void *o, int32_t Hq, int32_t d, uint32_t flags) {
     if (flags != DEFT_OUT_BF16 && flags != DEFT_OUT_F32) return DEFT_EINVAL;
     if (plan->nq == 0) return DEFT_OK;
-    if (!o || (reinterpret_cast<uintptr_t>(o) & 3)) return DEFT_EINVAL;
+    if (!o || !aligned16(o)) return DEFT_EINVAL;
     const deft::Schedule &S = *call.S;
     auto at = [&](size_t off) { return reinterpret_cast<const int32_t *>(call.img + off); };
     Stage2Args a2{};
@@ -969,7 +1017,7 @@ extern "C" int deft_tree_attn_decode(const deft_plan_t *plan, const void *dev_im
     if (rc != DEFT_OK) return rc;
     // check both stages' arguments before launching anything
     if (flags != DEFT_OUT_BF16 && flags != DEFT_OUT_F32) return DEFT_EINVAL;
-    if (plan->nq > 0 && (!o || (reinterpret_cast<uintptr_t>(o) & 3))) return DEFT_EINVAL;
+    if (plan->nq > 0 && (!o || !aligned16(o))) return DEFT_EINVAL;
     rc = run_stage1(plan, call, q, k, v, Hq, Hkv, d);
     if (rc != DEFT_OK) return rc;
     return run_stage2(plan, call, o, Hq, d, flags);

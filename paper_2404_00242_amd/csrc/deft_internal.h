@@ -33,7 +33,10 @@ enum ItemField {
     kItBegin0 = 9,    // first segment: physical row of its first token,
     kItSegQlo0 = 10,  //                its query interval
     kItSegQhi0 = 11,
+    kItPrecise = 12,  // 1: the softmax weights enter the products as two bf16 terms (short paths, or on request)
 };
+// A group one of whose queries has fewer tokens than this on its whole path gets two-term weights.
+constexpr int kPreciseBelowTokens = 1024;
 
 // Launch schedule + image layout for one Hq/Hkv ratio.
 struct Schedule {
@@ -46,6 +49,7 @@ struct Schedule {
     size_t off_q_head = 0;    // per-query records for stage 2
     size_t off_items = 0;     // task descriptors
     int32_t n_items = 0;
+    int32_t n_items_precise = 0;  // the last n_items_precise tasks of the list want two-term weights
     int32_t table_len = 32;   // longest chunk made of several pieces, rounded up to whole blocks: LDS table size
     std::vector<uint8_t> host_image;  // packed image, kept for repeated uploads
 };
@@ -55,6 +59,8 @@ struct Schedule {
 struct deft_plan_s {
     int32_t chunk_size = 0, n_nodes = 0, nq = 0, ntok = 0, n_flat = 0;
     uint32_t mode = 0;  // DEFT_SPLIT_* / DEFT_GROUP_QUERY
+    bool precise_all = false;  // DEFT_PRECISE_WEIGHTS was given
+    std::vector<int32_t> q_path_len;  // tokens on the whole path of plan position p (saturating)
     std::vector<int32_t> q_order, node_q_lo, node_q_hi;
     std::vector<int32_t> chunk_seg_ptr, seg_tok_begin, seg_len, seg_qlo, seg_qhi, seg_node;
     std::vector<int32_t> chunk_qlo, chunk_qhi, chunk_slot_base;

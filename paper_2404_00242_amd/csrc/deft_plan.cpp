@@ -65,8 +65,9 @@ struct NodeExtents {
 int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t *node_parent, int32_t n_nodes,
               const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size, uint32_t flags,
               deft_plan_t **out_plan) {
-    if (n_nodes < 1 || nq < 0 || ntok < 0 || flags > DEFT_GROUP_QUERY) return DEFT_EINVAL;
-    const uint32_t mode = flags;
+    if (n_nodes < 1 || nq < 0 || ntok < 0) return DEFT_EINVAL;
+    const uint32_t mode = flags & ~(uint32_t)DEFT_PRECISE_WEIGHTS;
+    if (mode > DEFT_GROUP_QUERY) return DEFT_EINVAL;
     if (nq > 0 && !query_node) return DEFT_EINVAL;
     if (chunk_size == 0) chunk_size = DEFT_DEFAULT_CHUNK;
     if (chunk_size < 0 || chunk_size % 32 != 0 || chunk_size > DEFT_MAX_CHUNK) return DEFT_EINVAL;
@@ -104,6 +105,7 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
         P->nq = nq;
         P->ntok = ntok;
         P->mode = mode;
+        P->precise_all = (flags & DEFT_PRECISE_WEIGHTS) != 0;
 
         // ---- depth-first renumbering of the queries ------------------------------------------
         // A node's own queries come first, then its subtrees, so the queries whose path contains u
@@ -134,6 +136,18 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
         {
             std::vector<int32_t> cursor = own_begin;  // next free plan position among u's own queries
             for (int32_t j = 0; j < nq; ++j) P->q_order[cursor[query_node[j]]++] = j;
+        }
+
+        // tokens on each query's whole path (parents come before children in preorder)
+        {
+            std::vector<int64_t> plen(n, 0);
+            for (int32_t i = 0; i < n; ++i) {
+                const int32_t u = pre[i], p = node_parent[u];
+                plen[u] = (p >= 0 ? plen[p] : 0) + node_tok_len[u];
+            }
+            P->q_path_len.resize(nq);
+            for (int32_t pos = 0; pos < nq; ++pos)
+                P->q_path_len[pos] = (int32_t)std::min<int64_t>(plen[query_node[P->q_order[pos]]], INT32_MAX);
         }
 
         // ---- the split: chunks as runs of node pieces ---------------------------------------------
@@ -484,6 +498,10 @@ static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
         const int32_t width = P->chunk_qhi[c] - P->chunk_qlo[c];
         const int64_t rows = (int64_t)width * G;
         const int32_t tiles = (int32_t)((rows + 15) / 16);
+        // two-term softmax weights where some query of the group has a short path
+        int32_t precise = P->precise_all ? 1 : 0;
+        for (int32_t p = P->chunk_qlo[c]; p < P->chunk_qhi[c] && !precise; ++p)
+            if (P->q_path_len[p] < kPreciseBelowTokens) precise = 1;
         for (int32_t t0 = 0; t0 < tiles; t0 += kMaxTilesPerTask) {
             int32_t d[kItemInts] = {0};
             d[kItChunk] = c;
@@ -498,6 +516,7 @@ static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
             d[kItBegin0] = P->seg_tok_begin[s0];
             d[kItSegQlo0] = P->seg_qlo[s0];
             d[kItSegQhi0] = P->seg_qhi[s0];
+            d[kItPrecise] = precise;
             items.insert(items.end(), d, d + kItemInts);
         }
     }
@@ -513,7 +532,14 @@ static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
         auto cost = [&](int32_t i) {
             return (int64_t)items[(size_t)i * kItemInts + kItLen] * (2 + items[(size_t)i * kItemInts + kItNTiles]);
         };
-        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return cost(x) > cost(y); });
+        auto precise = [&](int32_t i) { return items[(size_t)i * kItemInts + kItPrecise]; };
+        // tasks with two-term weights run in a kernel of their own and come last in the list
+        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+            if (precise(x) != precise(y)) return precise(x) < precise(y);
+            return cost(x) > cost(y);
+        });
+        S.n_items_precise = 0;
+        for (int32_t i = 0; i < n; ++i) S.n_items_precise += precise(i);
         std::vector<int32_t> sorted(items.size());
         for (int32_t i = 0; i < n; ++i)
             std::memcpy(&sorted[(size_t)i * kItemInts], &items[(size_t)order[i] * kItemInts], kItemInts * sizeof(int32_t));

@@ -56,9 +56,9 @@ def test_decode_iterations_on_a_changing_tree_match_the_oracle(seed, page_size):
         got = binding.deft_tree_attn_decode(plan, Q.cuda(), Kd, Vd, out_dtype=torch.float32)
         torch.cuda.synchronize()
         ref = oracle.tree_attention_paged(Q, K, V, pp, pg, page_size, nl, par, qn)
-        abs_v = oracle.tree_attention_paged(Q, K, V.abs(), pp, pg, page_size, nl, par, qn)
         got = got.cpu().numpy().astype(np.float64)
         err = np.abs(got - ref)
         print(f"    iteration {it}: nodes={len(nl)} queries={len(qn)} chunk={chunk} max|err|={err.max():.3e}", flush=True)
-        u = 2.0 ** -8  # bf16 weights: |err| <= 2u * attention over |V|
-        assert (err <= 2 * u * abs_v + u * np.abs(ref) + 1e-5).all()
+        # the stated tolerance, element-wise and per (query, head) row
+        assert (err <= 2e-3 + 1e-2 * np.abs(ref)).all()
+        assert (np.sqrt((err ** 2).sum(-1)) <= 1e-2 * np.sqrt((ref ** 2).sum(-1))).all()

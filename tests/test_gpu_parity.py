@@ -1,15 +1,16 @@
 """HIP path (through the C ABI) against the fp64 oracle, element by element.  Needs an MI355X.
 
-Tolerance (bf16 inputs, fp32 accumulation, bf16 probabilities in the P.V product):
+Tolerance (bf16 inputs, fp32 accumulation), the stated one, on every tree:
   * the five benchmark configurations: max |err| <= 2e-3 over all elements AND, per (query, head)
     row, ||err||_2 / ||ref||_2 <= 1e-2;
-  * arbitrary small trees, whose short paths give outputs of magnitude O(1) where one bf16 ulp
-    already exceeds 2e-3: the bound that follows from the arithmetic.  With u = 2^-8 the unit
-    roundoff of bf16, every softmax weight enters the P.V product with a relative error of at
-    most u and the denominator is the sum of the same rounded weights, so a normalised weight is
-    off by at most 2u of itself and an output element by at most 2u * sum_t w_t |V[t, c]|; the
-    bf16 output adds u |ref|.  sum_t w_t |V[t, c]| is the oracle's attention over |V|.
-    Element-wise |err| <= 2u * attention(|V|) + u |ref| + 1e-5, and the same row-relative bound.
+  * every other tree: element-wise |err| <= 2e-3 + 1e-2 |ref| and the same row-relative bound (short
+    paths give outputs of magnitude O(1), where half a bf16 ulp of the *output* already exceeds 2e-3,
+    hence the relative term).
+Stage 1 rounds softmax weights to bf16 for its matrix products.  Groups that contain a query with fewer
+than 1024 tokens on its path use two-term weights (hi + lo bf16, relative error 2^-17), so for trees whose
+paths are all that short and fp32 output the error is bounded far below the stated tolerance:
+|err| <= 2^-13 * sum_t w_t |V[t, c]| + 1e-5, which is checked too (sum_t w_t |V[t, c]| is the oracle's
+attention over |V|).
 """
 
 import numpy as np
@@ -23,7 +24,8 @@ from paper_2404_00242_amd import binding, workloads as wl
 pytestmark = pytest.mark.gpu
 
 ABS_TOL, REL_TOL = 2e-3, 1e-2
-U_BF16 = 2.0 ** -8
+PRECISE_BELOW = 1024     # tokens on a path below which the library uses two-term weights
+U_PRECISE = 2.0 ** -13   # bound on the relative error of a two-term weight and the fp32 sums, with margin
 
 
 def run_gpu(t, Q, K, V, chunk_size=0, out_dtype=torch.bfloat16, scale=0.0, mode="flatten"):
@@ -54,16 +56,40 @@ def errors(got, ref):
     return err, rel
 
 
-def check(got, ref, strict, abs_v=None):
-    """strict: the benchmark configurations' bound; otherwise abs_v = reference_abs_v(...) gives the bound"""
+def longest_and_shortest_path(t):
+    lens = []
+    for u in t.query_node:
+        u, n = int(u), 0
+        while u >= 0:
+            n += int(t.node_tok_len[u])
+            u = int(t.node_parent[u])
+        lens.append(n)
+    return (max(lens), min(lens)) if lens else (0, 0)
+
+
+def all_paths_short(t):
+    """every query's path is short enough for the library to use two-term weights in every group"""
+    return longest_and_shortest_path(t)[0] < PRECISE_BELOW
+
+
+def check(got, ref, strict, abs_v=None, two_term=False):
+    """strict: the benchmark configurations' bound, otherwise the element-wise form of the same tolerance.
+    two_term (fp32 output, every path short enough for two-term weights) adds the tight bound, for which
+    abs_v = reference_abs_v(...)."""
     assert np.isfinite(got).all()
     err, rel = errors(got, ref)
-    print(f"    max|err|={err.max():.3e} max row-rel={rel.max():.3e} max|ref|={np.abs(ref).max():.3f}", flush=True)
+    above = float((err > ABS_TOL).mean())
+    print(f"    max|err|={err.max():.3e} max row-rel={rel.max():.3e} max|ref|={np.abs(ref).max():.3f} "
+          f"share of elements above 2e-3: {above:.2e}", flush=True)
     if strict:
         assert err.max() <= ABS_TOL
     else:
-        assert (err <= 2 * U_BF16 * abs_v + U_BF16 * np.abs(ref) + 1e-5).all()
+        assert (err <= ABS_TOL + REL_TOL * np.abs(ref)).all()
     assert rel.max() <= REL_TOL
+    if two_term:
+        frac = err / (U_PRECISE * abs_v + 1e-5)
+        print(f"    two-term weights: largest error as a fraction of 2^-13 attention(|V|) + 1e-5: {frac.max():.3f}", flush=True)
+        assert frac.max() <= 1.0
 
 
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
@@ -130,7 +156,8 @@ def test_stage1_partials_match_algorithm4_and_stage2_completes_them():
                                           ws.data_ptr(), ws.numel(), st)
     assert rc == 0
     torch.cuda.synchronize()
-    check(o.cpu().numpy().astype(np.float64), reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V))
+    check(o.cpu().numpy().astype(np.float64), reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V),
+          two_term=all_paths_short(t))
 
 
 @pytest.mark.parametrize("mode", ["node", "node_chunk", "query"])
@@ -147,7 +174,7 @@ def test_other_partitioning_strategies_give_the_same_attention(mode):
                            n_roots=1 + seed % 2)
         Q, K, V = wl.make_qkv(t)
         got, _ = run_gpu(t, Q, K, V, chunk_size=64, out_dtype=torch.float32, mode=mode)
-        check(got, reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V))
+        check(got, reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V), two_term=all_paths_short(t))
 
 
 def test_tiny_variant_with_320_tokens():
@@ -180,9 +207,9 @@ def test_random_forests(seed):
     ref, abs_v = reference(t, Q, K, V), reference_abs_v(t, Q, K, V)
     for chunk in (32, 128):
         got, _ = run_gpu(t, Q, K, V, chunk_size=chunk, out_dtype=torch.float32)
-        check(got, ref, strict=False, abs_v=abs_v)
+        check(got, ref, strict=False, abs_v=abs_v, two_term=all_paths_short(t))
     got, _ = run_gpu(t, Q, K, V, chunk_size=64)
-    check(got, ref, strict=False, abs_v=abs_v)
+    check(got, ref, strict=False)
 
 
 def test_wide_groups_and_many_row_tiles():
@@ -190,20 +217,21 @@ def test_wide_groups_and_many_row_tiles():
     t = wl._finish("star", [300] + [5] * 150, [-1] + [0] * 150, list(range(1, 151)), 8, 2, 128, 77)
     Q, K, V = wl.make_qkv(t)
     got, _ = run_gpu(t, Q, K, V, out_dtype=torch.float32)
-    check(got, reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V))
+    check(got, reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V), two_term=True)
 
 
 def test_explicit_scale_and_empty_paths():
     t = wl.random_tree(3, n_nodes=6, max_len=50, nq=5, Hq=4, Hkv=2, d=128)
     Q, K, V = wl.make_qkv(t)
     got, _ = run_gpu(t, Q, K, V, out_dtype=torch.float32, scale=0.31)
-    check(got, reference(t, Q, K, V, scale=0.31), strict=False, abs_v=reference_abs_v(t, Q, K, V, scale=0.31))
+    check(got, reference(t, Q, K, V, scale=0.31), strict=False, abs_v=reference_abs_v(t, Q, K, V, scale=0.31),
+          two_term=True)
     # queries whose path has no token: zeros, and no kernel reads K/V
     t2 = wl._finish("empty", [0, 0, 7], [-1, 0, -1], [1, 1, 2], 4, 2, 64, 5, begins=[0, 0, 0], ntok=7)
     Q, K, V = wl.make_qkv(t2)
     got, _ = run_gpu(t2, Q, K, V, out_dtype=torch.float32)
     assert np.all(got[:2] == 0)
-    check(got, reference(t2, Q, K, V), strict=False, abs_v=reference_abs_v(t2, Q, K, V))
+    check(got, reference(t2, Q, K, V), strict=False, abs_v=reference_abs_v(t2, Q, K, V), two_term=True)
     # no queries at all
     t3 = wl._finish("noq", [9], [-1], [], 4, 2, 64, 5)
     Q, K, V = wl.make_qkv(t3)
@@ -307,7 +335,7 @@ def test_head_counts_that_do_not_divide_the_dispatch_round(Hq, Hkv, d):
     Q, K, V = wl.make_qkv(t)
     got, plan = run_gpu(t, Q, K, V, chunk_size=32, out_dtype=torch.float32)
     assert plan.view()["n_chunks"] * Hkv > 512
-    check(got, reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V))
+    check(got, reference(t, Q, K, V), strict=False)
 
 
 def test_rows_beyond_four_gigabytes_are_addressed_correctly():
@@ -331,7 +359,7 @@ def test_rows_beyond_four_gigabytes_are_addressed_correctly():
     plan = binding.deft_plan(begins_far, lens, parents, qn, n_rows, 64)
     got = binding.deft_tree_attn_decode(plan, Q.cuda(), k, v, out_dtype=torch.float32)
     torch.cuda.synchronize()
-    check(got.cpu().numpy().astype(np.float64), ref, strict=False, abs_v=abs_v)
+    check(got.cpu().numpy().astype(np.float64), ref, strict=False, abs_v=abs_v, two_term=True)
 
 
 def test_decode_calls_captured_in_a_hip_graph_replay_to_the_eager_result():
@@ -377,8 +405,7 @@ def test_decode_calls_captured_in_a_hip_graph_replay_to_the_eager_result():
         for i in range(L):
             assert torch.equal(got[i], want[i]), (rep, i)
     ref = reference(t, qs[0].cpu(), ks[0].cpu(), vs[0].cpu())
-    abs_v = reference_abs_v(t, qs[0].cpu(), ks[0].cpu(), vs[0].cpu())
-    check(got[0].float().cpu().numpy().astype(np.float64), ref, strict=False, abs_v=abs_v)
+    check(got[0].float().cpu().numpy().astype(np.float64), ref, strict=False)
 
 
 def test_randomised_sweep_of_shapes_strategies_and_storage():
@@ -386,7 +413,8 @@ def test_randomised_sweep_of_shapes_strategies_and_storage():
     (contiguous / paged) drawn independently for each, a quarter of them with long nodes and wide groups."""
     rng = np.random.default_rng(2024)
     modes = list(binding.SPLIT_MODES)
-    worst = 0.0
+    worst = worst_abs = worst_rel = 0.0
+    n_short = 0
     for it in range(120):
         Hkv = int(rng.choice([1, 2, 3, 4, 8]))
         G = int(rng.choice([1, 2, 4, 5, 8]))
@@ -416,10 +444,19 @@ def test_randomised_sweep_of_shapes_strategies_and_storage():
         torch.cuda.synchronize()
         got = got.cpu().numpy().astype(np.float64)
         assert np.isfinite(got).all(), case
-        frac = np.abs(got - ref) / (2 * U_BF16 * abs_v + 1e-5)
-        worst = max(worst, float(frac.max()))
-        assert frac.max() <= 1.0, case
-    print(f"\n    120 cases, largest error as a fraction of the bound: {worst:.3f}", flush=True)
+        err, rel = errors(got, ref)
+        assert (err <= ABS_TOL + REL_TOL * np.abs(ref)).all(), case
+        assert rel.max() <= REL_TOL, case
+        worst_abs = max(worst_abs, float((err / (ABS_TOL + REL_TOL * np.abs(ref))).max()))
+        worst_rel = max(worst_rel, float(rel.max()))
+        if all_paths_short(t):
+            n_short += 1
+            frac = err / (U_PRECISE * abs_v + 1e-5)
+            worst = max(worst, float(frac.max()))
+            assert frac.max() <= 1.0, case
+    print(f"\n    120 cases: largest error as a fraction of 2e-3 + 1e-2|ref|: {worst_abs:.3f}; largest row-relative "
+          f"error {worst_rel:.2e}; {n_short} trees with short paths only, largest error as a fraction of the "
+          f"two-term bound: {worst:.3f}", flush=True)
 
 
 def test_uploads_are_only_enqueued_and_may_outrun_the_stream():
@@ -445,4 +482,5 @@ def test_uploads_are_only_enqueued_and_may_outrun_the_stream():
         del plan
     torch.cuda.synchronize()
     for (t, Q, K, V, *_), o in zip(cases, outs):
-        check(o.cpu().numpy().astype(np.float64), reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V))
+        check(o.cpu().numpy().astype(np.float64), reference(t, Q, K, V), strict=False,
+              abs_v=reference_abs_v(t, Q, K, V), two_term=all_paths_short(t))

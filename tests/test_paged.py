@@ -104,9 +104,6 @@ def test_gpu_paged_random_trees(seed, page_size):
     t, (Q, K, V), (pp, pg, npool), (Kp, Vp), _ = paged_case(700 + seed, page_size, n_nodes=4 + 3 * seed, max_len=150,
                                                                nq=3 + 5 * seed, Hq=8, Hkv=2, d=128, n_roots=1 + seed % 2)
     ref = oracle.tree_attention_paged(Q, Kp, Vp, pp, pg, page_size, t.node_tok_len, t.node_parent, t.query_node)
-    # bound from the arithmetic: bf16 weights (unit roundoff u = 2^-8) over the oracle's attention on |V|
-    abs_v = oracle.tree_attention_paged(Q, Kp, Vp.abs(), pp, pg, page_size, t.node_tok_len, t.node_parent, t.query_node)
-    u = 2.0 ** -8
     dev = torch.device("cuda:0")
     for chunk in (64, 256):
         plan = binding.deft_plan_paged(pp, pg, page_size, npool, t.node_tok_len, t.node_parent, t.query_node, chunk)
@@ -114,7 +111,11 @@ def test_gpu_paged_random_trees(seed, page_size):
         torch.cuda.synchronize()
         got = got.cpu().numpy().astype(np.float64)
         err = np.abs(got - ref)
-        assert np.isfinite(got).all() and (err <= 2 * u * abs_v + u * np.abs(ref) + 1e-5).all(), err.max()
+        num, den = np.sqrt((err ** 2).sum(-1)), np.sqrt((ref ** 2).sum(-1))
+        print(f"    chunk {chunk}: max|err|={err.max():.3e} max row-rel={(num / np.maximum(den, 1e-300)).max():.3e}", flush=True)
+        # the stated tolerance, element-wise and per (query, head) row
+        assert np.isfinite(got).all() and (err <= 2e-3 + 1e-2 * np.abs(ref)).all(), err.max()
+        assert (num <= 1e-2 * den).all()
 
 
 @pytest.mark.gpu
