@@ -249,6 +249,24 @@ int deft_stage2_global_reduction(const deft_plan_t *plan, const void *dev_image,
                                  void *stream);
 
 /*
+ * deft_tree_attn_decode for callers that cannot allocate device memory or hold a workspace of their own
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the partial results
+ * live in a fixed array of DEFT_STATIC_SCRATCH_BYTES bytes that is part of the library's device code, one
+ * copy per GPU, kept until the process ends.  The call allocates nothing and frees nothing.  Arguments,
+ * results and errors are those of deft_tree_attn_decode without the workspace pair; a plan whose
+ * deft_workspace_bytes(plan, Hq, Hkv, d) exceeds DEFT_STATIC_SCRATCH_BYTES is refused with DEFT_EWORKSPACE
+ * and nothing is launched (use a larger chunk_size, or the call with a caller workspace).  All calls on one
+ * GPU share that GPU's array: calls that may overlap on one GPU (different streams, no ordering) race and
+ * must be ordered by the caller; the array keeps the last call's partial results and needs no clearing,
+ * because stage 2 only reads what stage 1 of the same call wrote.  The first call on a device looks up the
+ * array's address and must not be made while a stream is being captured.
+ */
+#define DEFT_STATIC_SCRATCH_BYTES (64u << 20)
+int deft_tree_attn_decode_static(const deft_plan_t *plan, const void *dev_image, const void *q, const void *k,
+                                 const void *v, void *o, int32_t Hq, int32_t Hkv, int32_t d, float scale,
+                                 uint32_t flags, void *stream);
+
+/*
  * Measurement aid: reads `bytes` bytes at dev_buf once with 128-bit loads from every compute unit
  * (DEFT_PROBE_SINK_BYTES / 4 workgroups, grid-stride) and stores, for each workgroup, the xor of the
  * 32-bit words it read into dev_sink (device, DEFT_PROBE_SINK_BYTES bytes, 4-byte aligned; all of it is

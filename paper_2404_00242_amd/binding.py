@@ -30,7 +30,7 @@ SPLIT_MODES = {"flatten": DEFT_SPLIT_FLATTEN, "node": DEFT_SPLIT_NODE, "node_chu
 
 EXPORTS = (
     "deft_plan", "deft_plan_paged", "deft_suggest_chunk_size", "deft_plan_view", "deft_plan_device_bytes", "deft_plan_upload", "deft_workspace_bytes",
-    "deft_tree_attn_decode", "deft_stage1_partial_attention", "deft_stage2_global_reduction",
+    "deft_tree_attn_decode", "deft_tree_attn_decode_static", "deft_stage1_partial_attention", "deft_stage2_global_reduction",
     "deft_hbm_read_probe", "deft_plan_destroy", "deft_strerror", "deft_last_hip_error",
 )
 
@@ -102,6 +102,9 @@ def load_library():
     lib.deft_tree_attn_decode.restype = ctypes.c_int
     lib.deft_tree_attn_decode.argtypes = [vp, vp, vp, vp, vp, vp, c32, c32, c32, ctypes.c_float, ctypes.c_uint32,
                                           vp, csz, vp]
+    lib.deft_tree_attn_decode_static.restype = ctypes.c_int
+    lib.deft_tree_attn_decode_static.argtypes = [vp, vp, vp, vp, vp, vp, c32, c32, c32, ctypes.c_float, ctypes.c_uint32,
+                                                 vp]
     lib.deft_stage1_partial_attention.restype = ctypes.c_int
     lib.deft_stage1_partial_attention.argtypes = [vp, vp, vp, vp, vp, c32, c32, c32, ctypes.c_float, vp, csz, vp]
     lib.deft_stage2_global_reduction.restype = ctypes.c_int

@@ -33,6 +33,11 @@
 
 #include "deft_internal.h"
 
+// Partial-result workspace of deft_tree_attn_decode_static: device memory inside the code object, one copy
+// per GPU at its own address, held until the process ends.  Host code never uses this name as an address;
+// it asks the runtime for the device address once per device (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[DEFT_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -1021,4 +1026,42 @@ extern "C" int deft_tree_attn_decode(const deft_plan_t *plan, const void *dev_im
     rc = run_stage1(plan, call, q, k, v, Hq, Hkv, d);
     if (rc != DEFT_OK) return rc;
     return run_stage2(plan, call, o, Hq, d, flags);
+}
+
+namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[64] = {};
+
+int static_scratch(void **out) {
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return DEFT_EHIP;
+    if (dev < 0 || dev >= 64) return DEFT_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "address of the static workspace")) return DEFT_EHIP;
+        if (!p || !aligned16(p)) return DEFT_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DEFT_OK;
+}
+
+}  // namespace
+
+extern "C" int deft_tree_attn_decode_static(const deft_plan_t *plan, const void *dev_image, const void *q,
+                                            const void *k, const void *v, void *o, int32_t Hq, int32_t Hkv, int32_t d,
+                                            float scale, uint32_t flags, void *stream) {
+    // size first: a plan whose partial results do not fit is refused before anything touches the device
+    const size_t need = deft_workspace_bytes(plan, Hq, Hkv, d);
+    if (need == 0) return DEFT_EINVAL;
+    if (need > (size_t)DEFT_STATIC_SCRATCH_BYTES) return DEFT_EWORKSPACE;
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != DEFT_OK) return rc;
+    // every (slot, head) stage 2 reads was written by stage 1 of the same call, so nothing has to be cleared
+    return deft_tree_attn_decode(plan, dev_image, q, k, v, o, Hq, Hkv, d, scale, flags, ws, DEFT_STATIC_SCRATCH_BYTES,
+                                 stream);
 }
