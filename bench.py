@@ -8,8 +8,11 @@ layer on its own K/V cache and queries, all resident in HBM before the clock sta
 caches per layer are what a real model has, and they keep every layer-call cold with respect to
 the 256 MB memory-side cache.
 
-Prints ONE JSON line: the metric is microseconds per layer-call (whole step divided by the number
-of layers, so the plan's cost is included pro rata), plus
+Prints ONE JSON line.  The headline (`value`, `roofline`, `cpu_baseline`) is the largest of the five
+benchmark workloads (config 5, the long-context tree) unless --config says otherwise; `per_config`
+carries the same measurements for all five workloads, taken in the same run.  The metric is
+microseconds per layer-call (whole step divided by the number of layers, so the plan's cost is
+included pro rata), plus
   roofline     stage-1 kernel: algorithmic KV bytes per launch / mean launch duration (HIP events on
                the launch stream, taken in a second pass over the same work) against the 8 TB/s peak
   cpu_baseline the fp64 oracle timed on this machine's host cores for one layer-call of the same workload
@@ -30,6 +33,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+TARGET_FRAC = 0.60  # of the HBM peak, the target stated for the long-prefix workloads
 
 
 def parse_args():
@@ -37,7 +41,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = few-shot, the headline)")
+    ap.add_argument("--config", type=int, default=5,
+                    help="workload of the headline numbers, 1..5 (5 = long-context tree, the largest)")
+    ap.add_argument("--only", action="store_true", help="measure the headline workload only (no per_config list)")
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--chunk", type=int, default=0,
                     help="S_t, tokens per chunk (0 = deft_suggest_chunk_size for this tree; 128 = the paper's default)")
@@ -50,24 +56,340 @@ def parse_args():
     ap.add_argument("--plain-alloc", action="store_true",
                     help="allocate every K and V pool with torch.empty (same alignment for both) instead of "
                          "binding.alloc_kv_cache, which staggers the V pool by half a KiB")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--precise", action="store_true", help="DEFT_PRECISE_WEIGHTS: two-term softmax weights everywhere")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle (no cpu_baseline, no parity check)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a few plain 1 GiB device-to-device copies (known size) so that a rocprofv3 "
                          "--pmc run of this command can scale its FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="bound on the oracle timing loop")
+    ap.add_argument("--sweep-chunk", action="store_true",
+                    help="instead of the benchmark: per workload, stage-1 time at the suggested S_t next to a sweep "
+                         "of chunk sizes (one JSON line with the table)")
     return ap.parse_args()
 
 
 def traffic_from_profiles(workload: str):
-    """HBM bytes per stage-1 launch measured with rocprofv3 --pmc, if a committed summary states it."""
-    path = os.path.join(ROOT, "profiles", "stage1_%s_hbm_traffic.txt" % workload)
+    """HBM bytes per stage-1 launch measured with rocprofv3 --pmc, if a committed summary states it.
+    Returns (bytes, file name) or (None, None): the figure is read from the file, not measured in this run."""
+    name = "stage1_%s_hbm_traffic.txt" % workload
+    path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
-        return None
+        return None, None
     for line in open(path):
         m = re.match(r"\s*TRAFFIC_BYTES_PER_LAUNCH\s+(\S+)\s*=\s*([0-9.eE+]+)", line)
         if m and m.group(1) == workload:
-            return float(m.group(2))
-    return None
+            return float(m.group(2)), "profiles/" + name
+    return None, None
+
+
+def percentiles(xs):
+    import numpy as np
+
+    a = np.asarray(xs, dtype=np.float64)
+    return {"median": round(float(np.median(a)), 3), "p10": round(float(np.percentile(a, 10)), 3),
+            "p90": round(float(np.percentile(a, 90)), 3), "mean": round(float(a.mean()), 3)}
+
+
+class Workload:
+    """One benchmark tree with per-layer Q/K/V resident in HBM and everything the C ABI needs to run it."""
+
+    def __init__(self, cfg, args, lib, dev):
+        import numpy as np
+        import torch
+
+        from paper_2404_00242_amd import binding, workloads
+
+        self.args, self.lib, self.dev = args, lib, dev
+        self.tree = tree = workloads.make_config(cfg)
+        self.Hq, self.Hkv, self.d, self.L = tree.Hq, tree.Hkv, tree.d, args.layers
+        Hq, Hkv, d, L = self.Hq, self.Hkv, self.d, self.L
+        self.Q0, self.K0, self.V0 = workloads.make_qkv(tree)  # layer 0: the seeded workload the parity tests use
+
+        # paged variant: the same tokens scattered over a pool of pages in random order
+        self.P = P = args.page_size
+        n_rows = tree.ntok
+        if P > 0:
+            self.page_ptr, self.page_ids, self.n_pool, row_of = workloads.to_paged(tree, P, seed=tree.value_seed)
+            n_rows = self.n_pool * P
+            K0p = workloads.scatter_to_pool(self.K0, row_of, n_rows, 1)
+            V0p = workloads.scatter_to_pool(self.V0, row_of, n_rows, 2)
+        else:
+            K0p, V0p = self.K0, self.V0
+
+        # per-layer inputs, resident in HBM
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(tree.value_seed)
+
+        def kv_pools():
+            if args.plain_alloc:
+                return (torch.empty((n_rows, Hkv, d), device=dev, dtype=torch.bfloat16),
+                        torch.empty((n_rows, Hkv, d), device=dev, dtype=torch.bfloat16))
+            return binding.alloc_kv_cache(n_rows, Hkv, d, dev)
+
+        self.qs, self.ks, self.vs, self.outs = [], [], [], []
+        for i in range(L):
+            k, v = kv_pools()
+            if i == 0:
+                self.qs.append(self.Q0.to(dev))
+                k.copy_(K0p)
+                v.copy_(V0p)
+            else:
+                self.qs.append(torch.randn((tree.nq, Hq, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
+                k.normal_(generator=gen)
+                v.normal_(generator=gen)
+            self.ks.append(k)
+            self.vs.append(v)
+        for _ in range(L):
+            self.outs.append(torch.empty((tree.nq, Hq, d), device=dev, dtype=torch.bfloat16))
+
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        self.nb = np.ascontiguousarray(tree.node_tok_begin, dtype=np.int32)
+        self.nl = np.ascontiguousarray(tree.node_tok_len, dtype=np.int32)
+        self.par = np.ascontiguousarray(tree.node_parent, dtype=np.int32)
+        self.qn = np.ascontiguousarray(tree.query_node, dtype=np.int32)
+        self.nbp, self.nlp, self.parp, self.qnp = (a.ctypes.data_as(i32p) for a in (self.nb, self.nl, self.par, self.qn))
+        if P > 0:
+            self.ppa = np.ascontiguousarray(self.page_ptr, dtype=np.int32)
+            self.pga = np.ascontiguousarray(self.page_ids, dtype=np.int32)
+            self.ppp, self.pgp = self.ppa.ctypes.data_as(i32p), self.pga.ctypes.data_as(i32p)
+        self.mode_flag = binding.SPLIT_MODES[args.mode] | (binding.DEFT_PRECISE_WEIGHTS if args.precise else 0)
+        self.stream = torch.cuda.current_stream(dev)
+        self.st = ctypes.c_void_p(self.stream.cuda_stream)
+        vp = ctypes.c_void_p
+        self.layer_ptrs = [(vp(self.qs[i].data_ptr()), vp(self.ks[i].data_ptr()), vp(self.vs[i].data_ptr()),
+                            vp(self.outs[i].data_ptr())) for i in range(L)]
+        self.plans = []
+        self.set_chunk(args.chunk)
+
+    def set_chunk(self, chunk):
+        """Fixes S_t (0 = the library's suggestion) and sizes the image buffer and the workspace for it."""
+        import torch
+
+        from paper_2404_00242_amd import binding
+
+        tree, Hq, Hkv, d = self.tree, self.Hq, self.Hkv, self.d
+        if chunk == 0:
+            chunk = binding.deft_suggest_chunk_size(self.nl, self.par, self.qn, Hq, Hkv)
+        self.chunk = chunk
+        if self.P > 0:
+            probe = binding.deft_plan_paged(self.ppa, self.pga, self.P, self.n_pool, self.nl, self.par, self.qn, chunk,
+                                            self.mode_flag)
+        else:
+            probe = binding.deft_plan(self.nb, self.nl, self.par, self.qn, tree.ntok, chunk, self.mode_flag)
+        self.view = probe.view()
+        self.img_bytes = probe.device_bytes(Hq, Hkv)
+        self.ws_bytes = probe.workspace_bytes(Hq, Hkv, d)
+        self.image = torch.empty(self.img_bytes, dtype=torch.uint8, device=self.dev)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
+        self.imgp, self.wsp = ctypes.c_void_p(self.image.data_ptr()), ctypes.c_void_p(self.ws.data_ptr())
+        # K and V of every reached token, once per KV head: what the method itself must move (a Q-guided plan
+        # moves more, but the useful bytes stay these)
+        n_reached = int(sum(int(self.nl[u]) for u in set(int(x) for x in self.view["seg_node"])))
+        self.kv_bytes = n_reached * Hkv * 2 * d * 2
+
+    def check(self, rc, what):
+        if rc != 0:
+            raise RuntimeError(f"{what} failed: {self.lib.deft_strerror(rc).decode()} {self.lib.deft_last_hip_error().decode()}")
+
+    def prepare(self):
+        # the upload is only enqueued (pinned staging inside the library), so the host prepares the next step
+        # while the GPU still runs this one; the copy is ordered behind this step's kernels on the stream, which
+        # is what makes reusing the one image buffer safe
+        lib, tree, Hq, Hkv = self.lib, self.tree, self.Hq, self.Hkv
+        h = ctypes.c_void_p()
+        if self.args.chunk == 0 and lib.deft_suggest_chunk_size(self.nlp, self.parp, tree.n_nodes, self.qnp, tree.nq, Hq, Hkv) < 0:
+            raise RuntimeError("deft_suggest_chunk_size failed")
+        if self.P > 0:
+            self.check(lib.deft_plan_paged(self.ppp, self.pgp, self.P, self.n_pool, self.nlp, self.parp, tree.n_nodes,
+                                           self.qnp, tree.nq, self.chunk, self.mode_flag, ctypes.byref(h)), "deft_plan_paged")
+        else:
+            self.check(lib.deft_plan(self.nbp, self.nlp, self.parp, tree.n_nodes, self.qnp, tree.nq, tree.ntok, self.chunk,
+                                     self.mode_flag, ctypes.byref(h)), "deft_plan")
+        if lib.deft_plan_device_bytes(h, Hq, Hkv) > self.img_bytes:
+            raise RuntimeError("plan image grew")
+        self.check(lib.deft_plan_upload(h, Hq, Hkv, self.imgp, self.img_bytes, self.st), "deft_plan_upload")
+        self.plans.append(h)
+        return h
+
+    def step(self):
+        lib, Hq, Hkv, d = self.lib, self.Hq, self.Hkv, self.d
+        h = self.prepare()
+        for (qp, kp, vpp, op) in self.layer_ptrs:
+            rc = lib.deft_tree_attn_decode(h, self.imgp, qp, kp, vpp, op, Hq, Hkv, d, 0.0, 0, self.wsp, self.ws_bytes, self.st)
+            if rc != 0:
+                self.check(rc, "deft_tree_attn_decode")
+        return h
+
+    def stage_times(self, n_rep):
+        """Per-stage durations (us per launch) with events on the launch stream.  Each stage's launches for all
+        layers run back to back between two events, so the mean includes the gap between two dispatches but
+        not the other stage."""
+        import torch
+
+        lib, Hq, Hkv, d, L = self.lib, self.Hq, self.Hkv, self.d, self.L
+        h = self.plans[-1] if self.plans else self.prepare()
+        s1, s2 = [], []
+        for _ in range(n_rep):
+            e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            e0.record(self.stream)
+            for (qp, kp, vpp, op) in self.layer_ptrs:
+                lib.deft_stage1_partial_attention(h, self.imgp, qp, kp, vpp, Hq, Hkv, d, 0.0, self.wsp, self.ws_bytes, self.st)
+            e1.record(self.stream)
+            for (qp, kp, vpp, op) in self.layer_ptrs:
+                lib.deft_stage2_global_reduction(h, self.imgp, op, Hq, Hkv, d, 0.0, 0, self.wsp, self.ws_bytes, self.st)
+            e2.record(self.stream)
+            torch.cuda.synchronize()
+            s1.append(e0.elapsed_time(e1) / L * 1e3)
+            s2.append(e1.elapsed_time(e2) / L * 1e3)
+        return s1, s2
+
+    def release(self):
+        for h in self.plans:
+            self.lib.deft_plan_destroy(h)
+        self.plans = []
+
+
+def measure(cfg, args, lib, dev, with_oracle, cpu_seconds):
+    """All measurements of one workload; returns (flat record for per_config, details for the headline)."""
+    import numpy as np
+    import torch
+
+    from paper_2404_00242_amd import workloads
+
+    w = Workload(cfg, args, lib, dev)
+    tree, L = w.tree, w.L
+    for _ in range(args.warmup):
+        w.step()
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    marks[0].record(w.stream)
+    for i in range(args.steps):
+        w.step()
+        marks[i + 1].record(w.stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    step_s = (t1 - t0) / max(args.steps, 1)
+    us_per_call = step_s * 1e6 / L
+    # per-step durations as the GPU saw them (the host runs ahead of the stream)
+    per_step_us = [marks[i].elapsed_time(marks[i + 1]) * 1e3 / L for i in range(args.steps)]
+    out_layer0 = w.outs[0].float().cpu().numpy().astype(np.float64)  # taken before the per-stage pass reuses the workspace
+
+    # host cost of the preparation phase alone
+    tp0 = time.perf_counter()
+    for _ in range(10):
+        w.prepare()
+    plan_us = (time.perf_counter() - tp0) * 1e5
+    torch.cuda.synchronize()
+
+    s1, s2 = w.stage_times(max(args.steps, 1))
+    s1_us, s2_us = float(np.mean(s1)), float(np.mean(s2))
+
+    # the same call with one replica only (layer 0 every time): the memory-side cache then holds part of K/V
+    h = w.plans[-1]
+    ew0, ew1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    qp, kp, vpp, op = w.layer_ptrs[0]
+    spare = torch.empty_like(w.outs[0])
+    ew0.record(w.stream)
+    for _ in range(L):
+        lib.deft_tree_attn_decode(h, w.imgp, qp, kp, vpp, ctypes.c_void_p(spare.data_ptr()), w.Hq, w.Hkv, w.d, 0.0, 0,
+                                  w.wsp, w.ws_bytes, w.st)
+    ew1.record(w.stream)
+    torch.cuda.synchronize()
+    warm_us = ew0.elapsed_time(ew1) / L * 1e3
+
+    # read-stream ceiling of this box: every layer's K and V read once by a plain 128-bit-load kernel
+    sink = torch.zeros(2048, dtype=torch.int32, device=dev)
+    buf_bytes = w.ks[0].numel() * 2
+    probe_ms = []
+    vp = ctypes.c_void_p
+    for _ in range(3):
+        ep0, ep1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ep0.record(w.stream)
+        for i in range(L):
+            w.check(lib.deft_hbm_read_probe(vp(w.ks[i].data_ptr()), buf_bytes, vp(sink.data_ptr()), w.st), "deft_hbm_read_probe")
+            w.check(lib.deft_hbm_read_probe(vp(w.vs[i].data_ptr()), buf_bytes, vp(sink.data_ptr()), w.st), "deft_hbm_read_probe")
+        ep1.record(w.stream)
+        torch.cuda.synchronize()
+        probe_ms.append(ep0.elapsed_time(ep1))
+    stream_gbs = 2 * L * buf_bytes / (min(probe_ms[1:]) * 1e-3) / 1e9
+
+    kv_bytes = w.kv_bytes
+    achieved = kv_bytes / (s1_us * 1e-6) / 1e9
+    whole = kv_bytes / (us_per_call * 1e-6) / 1e9
+    traffic, traffic_file = (traffic_from_profiles(tree.name) if args.mode == "flatten" and w.P == 0 and not args.precise
+                             else (None, None))
+    rec = {
+        "workload": tree.name, "us_per_layer_call": round(us_per_call, 3),
+        "us_per_layer_call_gpu_steps": percentiles(per_step_us),
+        "stage1_us": round(s1_us, 3), "stage2_us": round(s2_us, 3),
+        "stage1_us_dist": percentiles(s1), "stage2_us_dist": percentiles(s2),
+        "kv_bytes": kv_bytes, "chunk_size": w.view["chunk_size"], "n_chunks": w.view["n_chunks"],
+        "n_slots": w.view["n_slots"],
+        "stage1_frac_of_peak": round(achieved / HBM_PEAK_GBS, 4),
+        "whole_call_frac_of_peak": round(whole / HBM_PEAK_GBS, 4),
+        "target_0.60_of_peak": ("latency-bound workload, no bandwidth target" if cfg == 1 else
+                                ("met" if whole / HBM_PEAK_GBS >= TARGET_FRAC else
+                                 ("stage 1 alone meets it, the whole call does not" if achieved / HBM_PEAK_GBS >= TARGET_FRAC
+                                  else "missed"))),
+        "plan_plus_upload_us": round(plan_us, 1),
+    }
+    detail = {
+        "tree": tree, "view": w.view, "step_s": step_s, "us_per_call": us_per_call, "per_step_us": per_step_us,
+        "s1_us": s1_us, "s2_us": s2_us, "warm_us": warm_us, "plan_us": plan_us, "stream_gbs": stream_gbs,
+        "kv_bytes": kv_bytes, "achieved": achieved, "traffic": traffic, "traffic_file": traffic_file, "P": w.P,
+    }
+
+    # parity of layer 0 and the CPU baseline: the oracle as it stands, on this box's host cores
+    if with_oracle:
+        import oracle
+
+        reps, used, ref = 0, 0, None
+        tc0 = time.perf_counter()
+        while True:
+            ref, used = oracle.tree_attention(w.Q0, w.K0, w.V0, w.nb, w.nl, w.par, w.qn, return_threads=True)
+            reps += 1
+            if time.perf_counter() - tc0 >= cpu_seconds:
+                break
+        cpu_us = (time.perf_counter() - tc0) / reps * 1e6
+        err = np.abs(out_layer0 - ref)
+        rel = np.sqrt((err ** 2).sum(-1)) / np.maximum(np.sqrt((ref ** 2).sum(-1)), 1e-300)
+        rec["layer0_max_abs_err"] = float(err.max())
+        rec["layer0_max_row_rel_err"] = float(rel.max())
+        rec["layer0_ok"] = bool(err.max() <= 2e-3 and rel.max() <= 1e-2)
+        rec["oracle_us"] = round(cpu_us, 1)
+        detail["cpu"] = {"us": cpu_us, "cores": used, "reps": reps}
+    w.release()
+    del w
+    torch.cuda.empty_cache()
+    return rec, detail
+
+
+def sweep_chunk(args, lib, dev):
+    """Per workload: stage-1 time at deft_suggest_chunk_size's S_t next to a sweep of chunk sizes."""
+    import numpy as np
+
+    table = []
+    for cfg in (2, 3, 4, 5):
+        w = Workload(cfg, args, lib, dev)
+        suggested = w.chunk
+        rows = {}
+        for chunk in sorted(set([128, 256, 384, 512, 640, 768, 1024, 1280, 1536, 2048, 3072, 4096, suggested])):
+            w.set_chunk(chunk)
+            w.prepare()
+            w.stage_times(2)
+            s1, s2 = w.stage_times(5)
+            rows[chunk] = (round(float(np.median(s1)), 2), round(float(np.median(s2)), 2))
+            w.release()
+        best = min(rows, key=lambda c: rows[c][0] + rows[c][1])
+        table.append({"workload": w.tree.name, "suggested": suggested, "suggested_s1_s2_us": rows[suggested],
+                      "best": best, "best_s1_s2_us": rows[best],
+                      "suggested_over_best": round(sum(rows[suggested]) / sum(rows[best]), 3),
+                      "sweep_s1_s2_us": {str(c): rows[c] for c in rows}})
+        del w
+        import torch
+        torch.cuda.empty_cache()
+    print(json.dumps({"chunk_sweep": table, "split": args.mode}), flush=True)
 
 
 def main():
@@ -76,7 +398,6 @@ def main():
         print("bench.py: this build runs on one GPU only (no collective path exists); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     from paper_2404_00242_amd import binding, workloads
@@ -94,235 +415,77 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    tree = workloads.make_config(args.config)
-    Hq, Hkv, d, L = tree.Hq, tree.Hkv, tree.d, args.layers
-    Q0, K0, V0 = workloads.make_qkv(tree)  # layer 0: the seeded workload the parity tests use
+    if args.sweep_chunk:
+        sweep_chunk(args, lib, dev)
+        return
 
-    # paged variant: the same tokens scattered over a pool of pages in random order
-    P = args.page_size
-    n_rows = tree.ntok
-    if P > 0:
-        page_ptr, page_ids, n_pool, row_of = workloads.to_paged(tree, P, seed=tree.value_seed)
-        n_rows = n_pool * P
-        K0p = workloads.scatter_to_pool(K0, row_of, n_rows, 1)
-        V0p = workloads.scatter_to_pool(V0, row_of, n_rows, 2)
-    else:
-        K0p, V0p = K0, V0
+    with_oracle = not args.no_cpu_baseline
+    per_config = []
+    head = None
+    order = [args.config] if args.only else [args.config] + [c for c in (1, 2, 3, 4, 5) if c != args.config]
+    for cfg in order:
+        # the headline workload's oracle timing is the cpu_baseline (bounded by --cpu-seconds, at least one full
+        # run); the others run the oracle once, for the parity figure
+        rec, detail = measure(cfg, args, lib, dev, with_oracle, args.cpu_seconds if cfg == args.config else 0.0)
+        per_config.append((cfg, rec))
+        if cfg == args.config:
+            head = (rec, detail)
+    per_config = [r for _, r in sorted(per_config, key=lambda x: x[0])]
 
-    # per-layer inputs, resident in HBM
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(tree.value_seed)
-    def kv_pools():
-        if args.plain_alloc:
-            return (torch.empty((n_rows, Hkv, d), device=dev, dtype=torch.bfloat16),
-                    torch.empty((n_rows, Hkv, d), device=dev, dtype=torch.bfloat16))
-        return binding.alloc_kv_cache(n_rows, Hkv, d, dev)
-
-    qs, ks, vs, outs = [], [], [], []
-    for i in range(L):
-        k, v = kv_pools()
-        if i == 0:
-            qs.append(Q0.to(dev))
-            k.copy_(K0p)
-            v.copy_(V0p)
-        else:
-            qs.append(torch.randn((tree.nq, Hq, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16))
-            k.copy_(torch.randn((n_rows, Hkv, d), generator=gen, device=dev, dtype=torch.float32))
-            v.copy_(torch.randn((n_rows, Hkv, d), generator=gen, device=dev, dtype=torch.float32))
-        ks.append(k)
-        vs.append(v)
-    for _ in range(L):
-        outs.append(torch.empty((tree.nq, Hq, d), device=dev, dtype=torch.bfloat16))
-
-    i32p = ctypes.POINTER(ctypes.c_int32)
-    nb = np.ascontiguousarray(tree.node_tok_begin, dtype=np.int32)
-    nl = np.ascontiguousarray(tree.node_tok_len, dtype=np.int32)
-    par = np.ascontiguousarray(tree.node_parent, dtype=np.int32)
-    qn = np.ascontiguousarray(tree.query_node, dtype=np.int32)
-    nbp, nlp, parp, qnp = (a.ctypes.data_as(i32p) for a in (nb, nl, par, qn))
-
-    if args.chunk == 0:
-        args.chunk = binding.deft_suggest_chunk_size(nl, par, qn, Hq, Hkv)
-
-    # sizes are a property of the tree: allocate the image buffer and the workspace once
-    mode_flag = binding.SPLIT_MODES[args.mode]
-    if P > 0:
-        ppa = np.ascontiguousarray(page_ptr, dtype=np.int32)
-        pga = np.ascontiguousarray(page_ids, dtype=np.int32)
-        ppp, pgp = ppa.ctypes.data_as(i32p), pga.ctypes.data_as(i32p)
-        probe = binding.deft_plan_paged(ppa, pga, P, n_pool, nl, par, qn, args.chunk, mode_flag)
-    else:
-        probe = binding.deft_plan(nb, nl, par, qn, tree.ntok, args.chunk, mode_flag)
-    view = probe.view()
-    img_bytes = probe.device_bytes(Hq, Hkv)
-    ws_bytes = probe.workspace_bytes(Hq, Hkv, d)
-    image = torch.empty(img_bytes, dtype=torch.uint8, device=dev)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    stream = torch.cuda.current_stream(dev)
-    st = ctypes.c_void_p(stream.cuda_stream)
-    vp = ctypes.c_void_p
-    layer_ptrs = [(vp(qs[i].data_ptr()), vp(ks[i].data_ptr()), vp(vs[i].data_ptr()), vp(outs[i].data_ptr()))
-                  for i in range(L)]
-    imgp, wsp = vp(image.data_ptr()), vp(ws.data_ptr())
-
-    def check(rc, what):
-        if rc != 0:
-            raise RuntimeError(f"{what} failed: {lib.deft_strerror(rc).decode()} {lib.deft_last_hip_error().decode()}")
-
-    def prepare():
-        # the upload is only enqueued (pinned staging inside the library), so the host prepares the next step
-        # while the GPU still runs this one; the copy is ordered behind this step's kernels on the stream, which
-        # is what makes reusing the one image buffer safe
-        h = vp()
-        if lib.deft_suggest_chunk_size(nlp, parp, tree.n_nodes, qnp, tree.nq, Hq, Hkv) < 0:
-            raise RuntimeError("deft_suggest_chunk_size failed")
-        if P > 0:
-            check(lib.deft_plan_paged(ppp, pgp, P, n_pool, nlp, parp, tree.n_nodes, qnp, tree.nq, args.chunk, mode_flag,
-                                      ctypes.byref(h)), "deft_plan_paged")
-        else:
-            check(lib.deft_plan(nbp, nlp, parp, tree.n_nodes, qnp, tree.nq, tree.ntok, args.chunk, mode_flag,
-                                ctypes.byref(h)), "deft_plan")
-        if lib.deft_plan_device_bytes(h, Hq, Hkv) > img_bytes:
-            raise RuntimeError("plan image grew")
-        check(lib.deft_plan_upload(h, Hq, Hkv, imgp, img_bytes, st), "deft_plan_upload")
-        return h
-
-    def step():
-        h = prepare()
-        for (qp, kp, vpp, op) in layer_ptrs:
-            rc = lib.deft_tree_attn_decode(h, imgp, qp, kp, vpp, op, Hq, Hkv, d, 0.0, 0, wsp, ws_bytes, st)
-            if rc != 0:
-                check(rc, "deft_tree_attn_decode")
-        return h
-
-    plans = []
-    for _ in range(args.warmup):
-        plans.append(step())
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        plans.append(step())
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    step_s = (t1 - t0) / max(args.steps, 1)
-    us_per_call = step_s * 1e6 / L
-    out_layer0 = outs[0].float().cpu().numpy().astype(np.float64)  # taken before the per-stage pass reuses the workspace
-
-    # host cost of the preparation phase alone
-    tp0 = time.perf_counter()
-    for _ in range(10):
-        plans.append(prepare())
-    plan_us = (time.perf_counter() - tp0) * 1e5
-
-    # second pass: per-stage durations with events on the launch stream.  Each stage's launches for all
-    # layers run back to back between two events, so the mean includes the gap between two dispatches
-    # but not the other stage.
-    h = plans[-1]
-    n_prof = max(args.steps, 1)
-    s1_ms, s2_ms = [], []
-    for _ in range(n_prof):
-        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-        e0.record(stream)
-        for (qp, kp, vpp, op) in layer_ptrs:
-            lib.deft_stage1_partial_attention(h, imgp, qp, kp, vpp, Hq, Hkv, d, 0.0, wsp, ws_bytes, st)
-        e1.record(stream)
-        for (qp, kp, vpp, op) in layer_ptrs:
-            lib.deft_stage2_global_reduction(h, imgp, op, Hq, Hkv, d, 0.0, 0, wsp, ws_bytes, st)
-        e2.record(stream)
-        torch.cuda.synchronize()
-        s1_ms.append(e0.elapsed_time(e1) / L)
-        s2_ms.append(e1.elapsed_time(e2) / L)
-    s1_us = float(np.mean(s1_ms)) * 1e3
-    s2_us = float(np.mean(s2_ms)) * 1e3
-
-    # the same call with one replica only (layer 0 every time): the memory-side cache then holds part of K/V
-    ew0, ew1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    qp, kp, vpp, op = layer_ptrs[0]
-    spare = torch.empty_like(outs[0])
-    ew0.record(stream)
-    for _ in range(L):
-        lib.deft_tree_attn_decode(h, imgp, qp, kp, vpp, vp(spare.data_ptr()), Hq, Hkv, d, 0.0, 0, wsp, ws_bytes, st)
-    ew1.record(stream)
-    torch.cuda.synchronize()
-    warm_us = ew0.elapsed_time(ew1) / L * 1e3
-
-    # read-stream ceiling of this machine: every layer's K and V read once by a plain 128-bit-load kernel
-    sink = torch.zeros(2048, dtype=torch.int32, device=dev)
-    buf_bytes = ks[0].numel() * 2
-    probe_ms = []
-    for _ in range(3):
-        ep0, ep1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        ep0.record(stream)
-        for i in range(L):
-            check(lib.deft_hbm_read_probe(vp(ks[i].data_ptr()), buf_bytes, vp(sink.data_ptr()), st), "deft_hbm_read_probe")
-            check(lib.deft_hbm_read_probe(vp(vs[i].data_ptr()), buf_bytes, vp(sink.data_ptr()), st), "deft_hbm_read_probe")
-        ep1.record(stream)
-        torch.cuda.synchronize()
-        probe_ms.append(ep0.elapsed_time(ep1))
-    stream_gbs = 2 * L * buf_bytes / (min(probe_ms[1:]) * 1e-3) / 1e9
-
-    # K and V of every reached token, once per KV head: what the method itself must move (a Q-guided plan
-    # moves more, but the useful bytes stay these)
-    n_reached = int(sum(int(nl[u]) for u in set(int(x) for x in view["seg_node"])))
-    kv_bytes = n_reached * Hkv * 2 * d * 2
-    achieved = kv_bytes / (s1_us * 1e-6) / 1e9
-    workload = tree.name
-
+    rec, dt = head
+    tree, view = dt["tree"], dt["view"]
     result = {
         "metric": "tree_attn_decode_us_per_layer_call",
-        "value": round(us_per_call, 3),
+        "value": round(dt["us_per_call"], 3),
         "unit": "us/layer-call",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(step_s * 1e3, 4),
+        "ms_per_step": round(dt["step_s"] * 1e3, 4),
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": workload, "split": args.mode, "page_size": P,
-            "kv_placement": "plain" if args.plain_alloc else "V pool %d B past K pool's alignment (mod 1 KiB)" % binding.KV_STAGGER_BYTES, "Hq": Hq, "Hkv": Hkv, "d": d, "ntok": tree.ntok, "nq": tree.nq,
-            "layers_per_step": L, "chunk_size": view["chunk_size"], "n_chunks": view["n_chunks"],
+            "workload": tree.name, "split": args.mode, "page_size": dt["P"],
+            "kv_placement": "plain" if args.plain_alloc else "V pool %d B past K pool's alignment (mod 1 KiB)" % binding.KV_STAGGER_BYTES,
+            "Hq": tree.Hq, "Hkv": tree.Hkv, "d": tree.d, "ntok": tree.ntok, "nq": tree.nq,
+            "layers_per_step": args.layers, "chunk_size": view["chunk_size"], "n_chunks": view["n_chunks"],
             "n_slots": view["n_slots"], "path_tokens": workloads.path_token_count(tree),
+            "weights": "two-term everywhere" if args.precise else "bf16, two-term for paths under 1024 tokens",
         },
-        "kv_gbs_whole_call": round(kv_bytes / (us_per_call * 1e-6) / 1e9, 1),
-        "kv_frac_of_peak_whole_call": round(kv_bytes / (us_per_call * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-        "stage1_us": round(s1_us, 3),
-        "stage2_us": round(s2_us, 3),
-        "warm_single_replica_us": round(warm_us, 3),
-        "plan_plus_upload_us": round(plan_us, 1),
+        "us_per_layer_call_gpu_steps": rec["us_per_layer_call_gpu_steps"],
+        "kv_gbs_whole_call": round(dt["kv_bytes"] / (dt["us_per_call"] * 1e-6) / 1e9, 1),
+        "kv_frac_of_peak_whole_call": rec["whole_call_frac_of_peak"],
+        "stage1_us": rec["stage1_us"],
+        "stage2_us": rec["stage2_us"],
+        "stage1_us_dist": rec["stage1_us_dist"],
+        "stage2_us_dist": rec["stage2_us_dist"],
+        "warm_single_replica_us": round(dt["warm_us"], 3),
+        "plan_plus_upload_us": rec["plan_plus_upload_us"],
         "roofline": {
             "kernel": "deft_stage1 (partial attention, one layer-call)",
-            "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "algorithmic_bytes": kv_bytes,
-            "read_stream_ceiling": round(stream_gbs, 1), "frac_of_read_stream": round(achieved / stream_gbs, 4),
-            "traffic": traffic_from_profiles(workload) if args.mode == "flatten" and P == 0 else None,
+            "bound": "hbm", "achieved": round(dt["achieved"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(dt["achieved"] / HBM_PEAK_GBS, 4), "algorithmic_bytes": dt["kv_bytes"],
+            "read_stream_ceiling": round(dt["stream_gbs"], 1),
+            "frac_of_read_stream": round(dt["achieved"] / dt["stream_gbs"], 4),
+            "traffic": dt["traffic"],
+            "traffic_source": (None if dt["traffic"] is None else
+                               "%s (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of an earlier run of this command; "
+                               "read from the file, not measured in this run)" % dt["traffic_file"]),
         },
     }
-
-    # parity of layer 0 and the CPU baseline: the oracle as it stands, on this machine's host cores
-    if not args.no_cpu_baseline:
-        import oracle
-
-        reps, used, ref = 0, 0, None
-        tc0 = time.perf_counter()
-        while True:
-            ref, used = oracle.tree_attention(Q0, K0, V0, nb, nl, par, qn, return_threads=True)
-            reps += 1
-            if time.perf_counter() - tc0 >= args.cpu_seconds:
-                break
-        cpu_us = (time.perf_counter() - tc0) / reps * 1e6
-        err = float(np.abs(out_layer0 - ref).max())
+    if "cpu" in dt:
+        c = dt["cpu"]
         result["cpu_baseline"] = {
-            "value": round(cpu_us, 1), "unit": "us/layer-call", "cores": used, "kind": "oracle",
-            "sample": f"one full layer-call of {workload} (fp64, all {tree.nq}x{Hq} query rows), mean of {reps} runs",
+            "value": round(c["us"], 1), "unit": "us/layer-call", "cores": c["cores"], "kind": "oracle",
+            "sample": f"one full layer-call of {tree.name} (fp64, all {tree.nq}x{tree.Hq} query rows), mean of {c['reps']} run(s)",
         }
-        result["parity_layer0"] = {"max_abs_err": err, "ok": bool(err <= 2e-3)}
-
-    for h in plans:
-        lib.deft_plan_destroy(h)
+        result["parity_layer0"] = {"max_abs_err": rec["layer0_max_abs_err"], "max_row_rel_err": rec["layer0_max_row_rel_err"],
+                                   "ok": rec["layer0_ok"]}
+    if not args.only:
+        result["per_config"] = per_config
     print(json.dumps(result), flush=True)
 
 
