@@ -34,6 +34,7 @@ enum ItemField {
     kItSegQlo0 = 10,  //                its query interval
     kItSegQhi0 = 11,
     kItPrecise = 12,  // 1: the softmax weights enter the products as two bf16 terms (short paths, or on request)
+    kItCostTiles = 13,  // host only: tiles of the largest task of this chunk, the key of the dispatch order
 };
 // A group one of whose queries has fewer tokens than this on its whole path gets two-term weights.
 constexpr int kPreciseBelowTokens = 1024;

@@ -502,11 +502,16 @@ static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
         int32_t precise = P->precise_all ? 1 : 0;
         for (int32_t p = P->chunk_qlo[c]; p < P->chunk_qhi[c] && !precise; ++p)
             if (P->q_path_len[p] < kPreciseBelowTokens) precise = 1;
-        for (int32_t t0 = 0; t0 < tiles; t0 += kMaxTilesPerTask) {
+        // Groups of more than kMaxTilesPerTask tiles become several tasks of (nearly) equal size: the row groups
+        // of one chunk then cost the same, are dispatched next to each other and find the chunk in L2 after the
+        // first of them has fetched it.
+        const int32_t n_tasks = (tiles + kMaxTilesPerTask - 1) / kMaxTilesPerTask;
+        const int32_t per_task = n_tasks ? (tiles + n_tasks - 1) / n_tasks : 0;
+        for (int32_t t0 = 0; t0 < tiles; t0 += per_task) {
             int32_t d[kItemInts] = {0};
             d[kItChunk] = c;
             d[kItTile0] = t0;
-            d[kItNTiles] = std::min<int32_t>(kMaxTilesPerTask, tiles - t0);
+            d[kItNTiles] = std::min<int32_t>(per_task, tiles - t0);
             d[kItSeg0] = s0;
             d[kItNSeg] = s1 - s0;
             d[kItQlo] = P->chunk_qlo[c];
@@ -517,20 +522,22 @@ static void build_schedule(const deft_plan_t *P, int32_t G, Schedule &S) {
             d[kItSegQlo0] = P->seg_qlo[s0];
             d[kItSegQhi0] = P->seg_qhi[s0];
             d[kItPrecise] = precise;
+            d[kItCostTiles] = per_task;
             items.insert(items.end(), d, d + kItemInts);
         }
     }
 
     // Dispatch order: workgroups are handed to compute units in the order of the task list, a new one
     // whenever a slot frees, so the longest tasks go first (tokens x (2 + row tiles) as the estimate) and
-    // the short ones fill the tail.  Equal estimates keep their chunk order, which leaves the row groups of
-    // one chunk next to each other (they re-read that chunk from the same L2).
+    // the short ones fill the tail.  The row groups of one chunk share one estimate (that of the largest of
+    // them) and equal estimates keep their chunk order, which leaves them next to each other: they re-read
+    // that chunk from the same L2 while it is still there.
     {
         const int32_t n = (int32_t)(items.size() / kItemInts);
         std::vector<int32_t> order(n);
         for (int32_t i = 0; i < n; ++i) order[i] = i;
         auto cost = [&](int32_t i) {
-            return (int64_t)items[(size_t)i * kItemInts + kItLen] * (2 + items[(size_t)i * kItemInts + kItNTiles]);
+            return (int64_t)items[(size_t)i * kItemInts + kItLen] * (2 + items[(size_t)i * kItemInts + kItCostTiles]);
         };
         auto precise = [&](int32_t i) { return items[(size_t)i * kItemInts + kItPrecise]; };
         // tasks with two-term weights run in a kernel of their own and come last in the list
