@@ -47,9 +47,12 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--chunk", type=int, default=0,
                     help="S_t, tokens per chunk (0 = deft_suggest_chunk_size for this tree; 128 = the paper's default)")
-    ap.add_argument("--mode", default="flatten", choices=["flatten", "node", "node_chunk", "query"],
-                    help="partitioning strategy of the plan (flatten = the paper's method and the headline; the others "
-                         "are its ablation / comparison strategies run on the same kernels)")
+    ap.add_argument("--mode", default="balanced", choices=["flatten", "node", "node_chunk", "query", "balanced"],
+                    help="partitioning strategy of the plan.  balanced (default): the flattened split with chunks "
+                         "weighed by tokens x rows, this build's MI355X variant of the paper's equal-token split; "
+                         "flatten: the paper's split (Remark 3.1), also measured and reported next to the default as "
+                         "`equal_token_split`; the others are the paper's ablation / comparison strategies on the "
+                         "same kernels")
     ap.add_argument("--page-size", type=int, default=0,
                     help="0: node-contiguous KV cache (the headline); P > 0: the same tree over a paged pool of "
                          "P-token pages handed out in random order (deft_plan_paged)")
@@ -68,10 +71,10 @@ def parse_args():
     return ap.parse_args()
 
 
-def traffic_from_profiles(workload: str):
+def traffic_from_profiles(workload: str, split: str):
     """HBM bytes per stage-1 launch measured with rocprofv3 --pmc, if a committed summary states it.
     Returns (bytes, file name) or (None, None): the figure is read from the file, not measured in this run."""
-    name = "stage1_%s_hbm_traffic.txt" % workload
+    name = "stage1_%s_%s_hbm_traffic.txt" % (workload, split)
     path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
         return None, None
@@ -152,7 +155,7 @@ class Workload:
             self.ppa = np.ascontiguousarray(self.page_ptr, dtype=np.int32)
             self.pga = np.ascontiguousarray(self.page_ids, dtype=np.int32)
             self.ppp, self.pgp = self.ppa.ctypes.data_as(i32p), self.pga.ctypes.data_as(i32p)
-        self.mode_flag = binding.SPLIT_MODES[args.mode] | (binding.DEFT_PRECISE_WEIGHTS if args.precise else 0)
+        self.set_split(args.mode)
         self.stream = torch.cuda.current_stream(dev)
         self.st = ctypes.c_void_p(self.stream.cuda_stream)
         vp = ctypes.c_void_p
@@ -160,6 +163,14 @@ class Workload:
                             vp(self.outs[i].data_ptr())) for i in range(L)]
         self.plans = []
         self.set_chunk(args.chunk)
+
+    def set_split(self, mode):
+        from paper_2404_00242_amd import binding
+
+        self.mode = mode
+        self.mode_flag = binding.SPLIT_MODES[mode] | (binding.DEFT_PRECISE_WEIGHTS if self.args.precise else 0)
+        if mode == "balanced":
+            self.mode_flag |= binding.rows_per_query(self.Hq // self.Hkv)
 
     def set_chunk(self, chunk):
         """Fixes S_t (0 = the library's suggestion) and sizes the image buffer and the workspace for it."""
@@ -169,7 +180,7 @@ class Workload:
 
         tree, Hq, Hkv, d = self.tree, self.Hq, self.Hkv, self.d
         if chunk == 0:
-            chunk = binding.deft_suggest_chunk_size(self.nl, self.par, self.qn, Hq, Hkv)
+            chunk = binding.deft_suggest_chunk_size(self.nl, self.par, self.qn, Hq, Hkv, self.mode_flag)
         self.chunk = chunk
         if self.P > 0:
             probe = binding.deft_plan_paged(self.ppa, self.pga, self.P, self.n_pool, self.nl, self.par, self.qn, chunk,
@@ -197,7 +208,7 @@ class Workload:
         # is what makes reusing the one image buffer safe
         lib, tree, Hq, Hkv = self.lib, self.tree, self.Hq, self.Hkv
         h = ctypes.c_void_p()
-        if self.args.chunk == 0 and lib.deft_suggest_chunk_size(self.nlp, self.parp, tree.n_nodes, self.qnp, tree.nq, Hq, Hkv) < 0:
+        if self.args.chunk == 0 and lib.deft_suggest_chunk_size(self.nlp, self.parp, tree.n_nodes, self.qnp, tree.nq, Hq, Hkv, self.mode_flag) < 0:
             raise RuntimeError("deft_suggest_chunk_size failed")
         if self.P > 0:
             self.check(lib.deft_plan_paged(self.ppp, self.pgp, self.P, self.n_pool, self.nlp, self.parp, tree.n_nodes,
@@ -258,21 +269,24 @@ def measure(cfg, args, lib, dev, with_oracle, cpu_seconds):
 
     w = Workload(cfg, args, lib, dev)
     tree, L = w.tree, w.L
-    for _ in range(args.warmup):
-        w.step()
-    torch.cuda.synchronize()
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    t0 = time.perf_counter()
-    marks[0].record(w.stream)
-    for i in range(args.steps):
-        w.step()
-        marks[i + 1].record(w.stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    step_s = (t1 - t0) / max(args.steps, 1)
+
+    def timed_steps(n_warm, n_steps):
+        for _ in range(n_warm):
+            w.step()
+        torch.cuda.synchronize()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_steps + 1)]
+        t0 = time.perf_counter()
+        marks[0].record(w.stream)
+        for i in range(n_steps):
+            w.step()
+            marks[i + 1].record(w.stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        # per-step durations as the GPU saw them (the host runs ahead of the stream)
+        return (t1 - t0) / max(n_steps, 1), [marks[i].elapsed_time(marks[i + 1]) * 1e3 / L for i in range(n_steps)]
+
+    step_s, per_step_us = timed_steps(args.warmup, args.steps)
     us_per_call = step_s * 1e6 / L
-    # per-step durations as the GPU saw them (the host runs ahead of the stream)
-    per_step_us = [marks[i].elapsed_time(marks[i + 1]) * 1e3 / L for i in range(args.steps)]
     out_layer0 = w.outs[0].float().cpu().numpy().astype(np.float64)  # taken before the per-stage pass reuses the workspace
 
     # host cost of the preparation phase alone
@@ -317,10 +331,10 @@ def measure(cfg, args, lib, dev, with_oracle, cpu_seconds):
     kv_bytes = w.kv_bytes
     achieved = kv_bytes / (s1_us * 1e-6) / 1e9
     whole = kv_bytes / (us_per_call * 1e-6) / 1e9
-    traffic, traffic_file = (traffic_from_profiles(tree.name) if args.mode == "flatten" and w.P == 0 and not args.precise
+    traffic, traffic_file = (traffic_from_profiles(tree.name, args.mode) if w.P == 0 and not args.precise and args.chunk == 0
                              else (None, None))
     rec = {
-        "workload": tree.name, "us_per_layer_call": round(us_per_call, 3),
+        "workload": tree.name, "split": args.mode, "us_per_layer_call": round(us_per_call, 3),
         "us_per_layer_call_gpu_steps": percentiles(per_step_us),
         "stage1_us": round(s1_us, 3), "stage2_us": round(s2_us, 3),
         "stage1_us_dist": percentiles(s1), "stage2_us_dist": percentiles(s2),
@@ -359,6 +373,19 @@ def measure(cfg, args, lib, dev, with_oracle, cpu_seconds):
         rec["layer0_ok"] = bool(err.max() <= 2e-3 and rel.max() <= 1e-2)
         rec["oracle_us"] = round(cpu_us, 1)
         detail["cpu"] = {"us": cpu_us, "cores": used, "reps": reps}
+    # the paper's equal-token split (Remark 3.1) on the same buffers, next to the default split
+    if args.mode != "flatten" and args.chunk == 0 and w.P == 0:
+        w.release()
+        w.set_split("flatten")
+        w.set_chunk(0)
+        f_step_s, _ = timed_steps(2, max(args.steps // 2, 3))
+        f1, f2 = w.stage_times(max(args.steps // 2, 3))
+        rec["equal_token_split"] = {
+            "us_per_layer_call": round(f_step_s * 1e6 / L, 3), "stage1_us": round(float(np.mean(f1)), 3),
+            "stage2_us": round(float(np.mean(f2)), 3), "chunk_size": w.view["chunk_size"],
+            "n_chunks": w.view["n_chunks"], "n_slots": w.view["n_slots"],
+            "stage1_frac_of_peak": round(kv_bytes / (float(np.mean(f1)) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+        }
     w.release()
     del w
     torch.cuda.empty_cache()

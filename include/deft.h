@@ -58,6 +58,21 @@ typedef enum deft_status {
 #define DEFT_SPLIT_NODE_CHUNK 2u
 #define DEFT_GROUP_QUERY 3u
 /*
+ * Not in the paper: the flattened split for a machine on which a chunk costs tokens x rows, not tokens.
+ * Remark 3.1 makes chunks of equal token count because decoding is bound by reading the KV cache; on an MI355X
+ * a chunk shared by hundreds of query rows is bound by the arithmetic instead, and a chunk that mixes a
+ * widely shared node with narrow ones pays every token for every row of the whole group.
+ *   DEFT_SPLIT_BALANCED    KV-guided; depth-first order as DEFT_SPLIT_FLATTEN, but a node piece joins the open
+ *                          chunk only if the joint chunk costs no more than the two apart plus a fixed cost of
+ *                          opening a chunk (cost of a chunk = tokens x t x (2 + tiles per task), for a group
+ *                          of `tiles` 16-row tiles worked on by t = ceil(tiles / 8) equal tasks; opening costs
+ *                          192), and a chunk may hold min(t, 4) * chunk_size tokens, so that widely shared
+ *                          prefixes produce fewer partial results.  Rows = queries of the group x query heads per
+ *                          KV head: or DEFT_ROWS_PER_QUERY(Hq / Hkv) to the flags (1 if absent).
+ */
+#define DEFT_SPLIT_BALANCED 4u
+#define DEFT_ROWS_PER_QUERY(g) (((uint32_t)(g) & 0xfffu) << 16)
+/*
  * May be or-ed to any of the above.  Stage 1 rounds the softmax weights to bf16 for its matrix products
  * (fp32 sums); a weight then carries a relative error of up to 2^-8.  Over a long path these errors average
  * out; a group one of whose queries has fewer than 1024 tokens on its whole path is therefore always
@@ -137,7 +152,9 @@ typedef struct deft_plan_view {
  *     and every call that sees the same tree.
  * Errors: DEFT_EINVAL for any malformed input (null pointer, n_nodes < 1, nq < 0, parent out
  *     of range or cyclic, range outside the cache or overlapping, query node out of range,
- *     bad chunk_size, unknown flags); DEFT_ENOMEM.  *out_plan is NULL on error.
+ *     bad chunk_size, unknown flags); DEFT_ENOMEM.  *out_plan is NULL on error.  With DEFT_SPLIT_NODE (or
+ *     DEFT_SPLIT_BALANCED over few, very wide nodes) a chunk may be longer than chunk_size; a chunk of more
+ *     than DEFT_MAX_CHUNK tokens that consists of several pieces (a paged node) is refused with DEFT_EINVAL.
  */
 int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_len, const int32_t *node_parent,
               int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size,
@@ -163,16 +180,19 @@ int deft_plan_paged(const int32_t *node_page_ptr, const int32_t *page_ids, int32
                     deft_plan_t **out_plan);
 
 /*
- * A chunk size S_t suited to this tree on an MI355X (the paper leaves S_t as a tuning knob, Fig. 11):
- * the multiple of 128 that makes the number of stage-1 tasks, (chunk, KV head, 128 rows of the chunk's
- * query group), about twice the number of compute units, so that every unit streams the same number of
- * KV bytes; at least 128 and at most 768, or at most 1024 when some group is wider than one task (fewer
- * partial results).  A heuristic from measurements, not an optimum.  Host arrays as for deft_plan (token
- * begins are not needed).  Returns the size, or a negative deft_status on malformed input.  Any valid
- * S_t gives the same attention result.
+ * A chunk size S_t suited to this tree on an MI355X (the paper leaves S_t as a tuning knob, Fig. 11).
+ * flags names the split the size is for (a DEFT_SPLIT_* / DEFT_GROUP_QUERY value; other bits are ignored).
+ * For DEFT_SPLIT_BALANCED: the multiple of 128 that gives about one stage-1 task per resident workgroup slot
+ * (two per compute unit) if all chunks were narrow, at least 128 and at most 768 (the split itself makes the
+ * chunks of widely shared nodes up to four times longer).  For the other splits: the multiple of 128 that
+ * makes the number of stage-1 tasks, (chunk, KV head, 128 rows of the chunk's query group), about twice the
+ * number of compute units, so that every unit streams the same number of KV bytes; at least 128 and at most
+ * 768, or at most 1024 when some group is wider than one task (fewer partial results).  Heuristics from
+ * measurements, not optima.  Host arrays as for deft_plan (token begins are not needed).  Returns the size,
+ * or a negative deft_status on malformed input.  Any valid S_t gives the same attention result.
  */
 int32_t deft_suggest_chunk_size(const int32_t *node_tok_len, const int32_t *node_parent, int32_t n_nodes,
-                                const int32_t *query_node, int32_t nq, int32_t Hq, int32_t Hkv);
+                                const int32_t *query_node, int32_t nq, int32_t Hq, int32_t Hkv, uint32_t flags);
 
 /* Fills *out with borrowed host pointers to the canonical arrays described above. */
 int deft_plan_view(const deft_plan_t *plan, deft_plan_view_t *out);

@@ -23,6 +23,16 @@ group per tree node), DeFT-Node-Chunk ("node_chunk": nodes cut into blocks) and
 Q-guided grouping with the Flash-Decoding split ("query": each query with its own
 path, shared prefixes repeated), which the ablations and the IO comparison need.
 
+Mode "balanced" is not in the paper.  Remark 3.1 cuts the flattened sequence into
+chunks of equal token count because, with decoding bound by the KV read, equal
+tokens mean equal cost (Section 3.3).  Where the cost of a chunk also grows with
+the number of query rows that share it, "balanced" keeps the depth-first order
+but weighs a chunk by tokens x rows: a node piece joins the open chunk only if
+the joint chunk is not dearer than the two apart (a chunk pays every one of its
+tokens for every row of its whole group), and a chunk shared by many rows may
+be up to four times longer (fewer partial results per row).  The cost model is
+stated in _balanced_weight; it is this build's, not the paper's.
+
 Everything is integer work; the output arrays are the canonical encoding that
 the C++ planner must reproduce bit for bit.
 """
@@ -67,19 +77,41 @@ def _validate(nb, nl, par, qn, ntok, chunk_size):
             raise PlanError("query node out of range")
 
 
-def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, chunk_size=128, mode="flatten"):
-    """The plan for a node-contiguous cache: node u owns rows [node_tok_begin[u], +node_tok_len[u])."""
+BALANCED_ROWS_PER_TILE = 16    # rows handled together (one matrix tile)
+BALANCED_TILES_PER_TASK = 8    # a chunk whose group has more tiles is worked on by several tasks
+BALANCED_OPEN_COST = 192       # fixed cost of opening a chunk: 64 tokens of a one-tile group
+BALANCED_MAX_STRETCH = 4       # a chunk of t tasks may hold min(t, 4) * chunk_size tokens,
+BALANCED_MAX_TOKENS = 4096     # but never more than this
+
+
+def _balanced_weight(width, rows_per_query):
+    """(cost of one token of a chunk shared by `width` queries, number of tasks that work on the chunk).
+
+    The group's rows (queries x query heads per KV head) are tiled BALANCED_ROWS_PER_TILE at a time; up to
+    BALANCED_TILES_PER_TASK tiles make one task, wider groups are split into equal tasks; a task spends 2 units
+    per token on fetching it and 1 per tile on the arithmetic."""
+    rows = width * rows_per_query
+    tiles = -(-rows // BALANCED_ROWS_PER_TILE)
+    tasks = max(1, -(-tiles // BALANCED_TILES_PER_TASK))
+    per_task = -(-tiles // tasks)
+    return tasks * (2 + per_task), tasks
+
+
+def flatten_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok, chunk_size=128, mode="flatten",
+                 rows_per_query=1):
+    """The plan for a node-contiguous cache: node u owns rows [node_tok_begin[u], +node_tok_len[u]).
+    rows_per_query (query heads per KV head) only matters to mode "balanced"."""
     nb = [int(x) for x in node_tok_begin]
     nl = [int(x) for x in node_tok_len]
     par = [int(x) for x in node_parent]
     qn = [int(x) for x in query_node]
     _validate(nb, nl, par, qn, int(ntok), int(chunk_size))
     ext = [[(nb[u], nl[u])] if nl[u] > 0 else [] for u in range(len(nb))]
-    return _plan(ext, nl, par, qn, int(chunk_size), mode)
+    return _plan(ext, nl, par, qn, int(chunk_size), mode, int(rows_per_query))
 
 
 def flatten_plan_paged(node_page_ptr, page_ids, page_size, n_pool_pages, node_tok_len, node_parent, query_node,
-                       chunk_size=128, mode="flatten"):
+                       chunk_size=128, mode="flatten", rows_per_query=1):
     """The plan for a paged cache (Section 4.2): token t of node u is row
     page_ids[node_page_ptr[u] + t // page_size] * page_size + t % page_size.  Pages that follow each other in
     the pool are joined into one run; segments are cut where a node's storage is not contiguous."""
@@ -112,11 +144,13 @@ def flatten_plan_paged(node_page_ptr, page_ids, page_size, n_pool_pages, node_to
                 runs.append((begin, cnt))
         ext.append(runs)
     _validate([0] * n, [0] * n, par, qn, npool * P, int(chunk_size))   # tree shape, query map, chunk size
-    return _plan(ext, nl, par, qn, int(chunk_size), mode)
+    return _plan(ext, nl, par, qn, int(chunk_size), mode, int(rows_per_query))
 
 
-def _plan(ext, nl, par, qn, B, mode):
+def _plan(ext, nl, par, qn, B, mode, G=1):
     n, nq = len(nl), len(qn)
+    if G < 1:
+        raise PlanError("rows_per_query must be positive")
 
     # 1. children lists, ascending node id
     children = [[] for _ in range(n)]
@@ -221,6 +255,34 @@ def _plan(ext, nl, par, qn, B, mode):
                     room -= take
             if cur:
                 chunks.append(cur)
+    elif mode == "balanced":
+        # depth-first order as in "flatten"; a piece joins the open chunk only if that is not dearer than a
+        # chunk of its own, and the length limit grows with the number of tasks the chunk's group needs
+        cur, cur_tokens, cur_lo, cur_hi = [], 0, 0, 0
+        for u in flat_nodes:
+            off = 0
+            while off < nl[u]:
+                left = nl[u] - off
+                if cur:
+                    lo, hi = min(cur_lo, q_lo[u]), max(cur_hi, q_hi[u])
+                    w_joint, tasks = _balanced_weight(hi - lo, G)
+                    take = min(left, min(B * min(tasks, BALANCED_MAX_STRETCH), BALANCED_MAX_TOKENS) - cur_tokens)
+                    w_cur, _ = _balanced_weight(cur_hi - cur_lo, G)
+                    w_own, _ = _balanced_weight(q_hi[u] - q_lo[u], G)
+                    if take <= 0 or (cur_tokens + take) * w_joint > cur_tokens * w_cur + take * w_own + BALANCED_OPEN_COST:
+                        chunks.append(cur)
+                        cur, cur_tokens = [], 0
+                        continue
+                else:
+                    lo, hi = q_lo[u], q_hi[u]
+                    _, tasks = _balanced_weight(hi - lo, G)
+                    take = min(left, min(B * min(tasks, BALANCED_MAX_STRETCH), BALANCED_MAX_TOKENS))
+                cur.extend((b, ln, q_lo[u], q_hi[u], u) for (b, ln) in node_range(u, off, take))
+                cur_tokens += take
+                cur_lo, cur_hi = lo, hi
+                off += take
+        if cur:
+            chunks.append(cur)
     else:
         raise PlanError("unknown split mode")
 

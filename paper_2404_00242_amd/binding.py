@@ -24,9 +24,15 @@ DEFT_SPLIT_FLATTEN = 0
 DEFT_SPLIT_NODE = 1
 DEFT_SPLIT_NODE_CHUNK = 2
 DEFT_GROUP_QUERY = 3
+DEFT_SPLIT_BALANCED = 4  # or rows_per_query(Hq // Hkv) to it
 DEFT_PRECISE_WEIGHTS = 0x100  # or-ed to a mode: two-term softmax weights in every group
 SPLIT_MODES = {"flatten": DEFT_SPLIT_FLATTEN, "node": DEFT_SPLIT_NODE, "node_chunk": DEFT_SPLIT_NODE_CHUNK,
-               "query": DEFT_GROUP_QUERY}
+               "query": DEFT_GROUP_QUERY, "balanced": DEFT_SPLIT_BALANCED}
+
+
+def rows_per_query(g: int) -> int:
+    """DEFT_ROWS_PER_QUERY(g): the flag bits that tell DEFT_SPLIT_BALANCED how many query heads share a KV head"""
+    return (int(g) & 0xFFF) << 16
 
 EXPORTS = (
     "deft_plan", "deft_plan_paged", "deft_suggest_chunk_size", "deft_plan_view", "deft_plan_device_bytes", "deft_plan_upload", "deft_workspace_bytes",
@@ -90,7 +96,7 @@ def load_library():
     lib.deft_plan_paged.argtypes = [_i32p, _i32p, c32, c32, _i32p, _i32p, c32, _i32p, c32, c32, ctypes.c_uint32,
                                     ctypes.POINTER(vp)]
     lib.deft_suggest_chunk_size.restype = ctypes.c_int32
-    lib.deft_suggest_chunk_size.argtypes = [_i32p, _i32p, c32, _i32p, c32, c32, c32]
+    lib.deft_suggest_chunk_size.argtypes = [_i32p, _i32p, c32, _i32p, c32, c32, c32, ctypes.c_uint32]
     lib.deft_plan_view.restype = ctypes.c_int
     lib.deft_plan_view.argtypes = [vp, ctypes.POINTER(_PlanView)]
     lib.deft_plan_device_bytes.restype = csz
@@ -213,12 +219,13 @@ def _stream_ptr(stream, device):
     return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
 
 
-def deft_suggest_chunk_size(node_tok_len, node_parent, query_node, Hq: int, Hkv: int) -> int:
-    """Chunk size S_t that gives about two equal stage-1 tasks per compute unit for this tree."""
+def deft_suggest_chunk_size(node_tok_len, node_parent, query_node, Hq: int, Hkv: int, flags: int = 0) -> int:
+    """Chunk size S_t suited to this tree for the split named by flags (about two equal stage-1 tasks per
+    compute unit)."""
     nl, par, qn = _i32(node_tok_len), _i32(node_parent), _i32(query_node)
     qptr = qn.ctypes.data_as(_i32p) if qn.size else None
     rc = load_library().deft_suggest_chunk_size(nl.ctypes.data_as(_i32p), par.ctypes.data_as(_i32p), nl.size, qptr,
-                                                qn.size, int(Hq), int(Hkv))
+                                                qn.size, int(Hq), int(Hkv), int(flags))
     if rc < 0:
         _check(rc, "deft_suggest_chunk_size")
     return int(rc)

@@ -66,8 +66,10 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
               const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size, uint32_t flags,
               deft_plan_t **out_plan) {
     if (n_nodes < 1 || nq < 0 || ntok < 0) return DEFT_EINVAL;
-    const uint32_t mode = flags & ~(uint32_t)DEFT_PRECISE_WEIGHTS;
-    if (mode > DEFT_GROUP_QUERY) return DEFT_EINVAL;
+    const uint32_t mode = flags & 0xffu;
+    const int32_t rows_per_query = (int32_t)((flags >> 16) & 0xfffu);  // DEFT_ROWS_PER_QUERY(g), 0 = not given
+    if ((flags & ~(0xffu | (uint32_t)DEFT_PRECISE_WEIGHTS | (0xfffu << 16))) != 0) return DEFT_EINVAL;
+    if (mode > DEFT_SPLIT_BALANCED) return DEFT_EINVAL;
     if (nq > 0 && !query_node) return DEFT_EINVAL;
     if (chunk_size == 0) chunk_size = DEFT_DEFAULT_CHUNK;
     if (chunk_size < 0 || chunk_size % 32 != 0 || chunk_size > DEFT_MAX_CHUNK) return DEFT_EINVAL;
@@ -249,12 +251,76 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
                 }
                 break;
             }
+            case DEFT_SPLIT_BALANCED: {
+                // Depth-first order as for DEFT_SPLIT_FLATTEN, but a chunk is weighed by tokens x rows: a piece joins
+                // the open chunk only if the joint chunk costs no more than the two apart plus the cost of opening
+                // one, and a chunk whose group needs t tasks may hold min(t, 4) * S tokens.
+                const int64_t G = rows_per_query > 0 ? rows_per_query : 1;
+                struct Weight {
+                    int64_t per_token, tasks;
+                };
+                auto weight = [&](int64_t width) {
+                    const int64_t tiles = (width * G + 15) / 16;
+                    const int64_t tasks = std::max<int64_t>(1, (tiles + 7) / 8);
+                    const int64_t per_task = (tiles + tasks - 1) / tasks;
+                    return Weight{tasks * (2 + per_task), tasks};
+                };
+                constexpr int64_t kOpenCost = 192, kMaxStretch = 4;
+                auto limit = [&](int64_t tasks) {
+                    return std::min<int64_t>(S * std::min(tasks, kMaxStretch), DEFT_MAX_CHUNK);
+                };
+                int64_t held = 0;
+                int32_t c_lo = 0, c_hi = 0;
+                for (int32_t i = 0; i < n; ++i) {
+                    const int32_t u = pre[i];
+                    if (!reached(u)) continue;
+                    const int32_t u_lo = P->node_q_lo[u], u_hi = P->node_q_hi[u];
+                    const Weight own = weight(u_hi - u_lo);
+                    int32_t done = 0;
+                    const int32_t len = node_tok_len[u];
+                    while (done < len) {
+                        const int64_t left = len - done;
+                        int32_t lo = u_lo, hi = u_hi;
+                        int64_t take;
+                        if (open) {
+                            lo = std::min(c_lo, u_lo);
+                            hi = std::max(c_hi, u_hi);
+                            const Weight joint = weight(hi - lo), cur = weight(c_hi - c_lo);
+                            take = std::min<int64_t>(left, limit(joint.tasks) - held);
+                            if (take <= 0 || (held + take) * joint.per_token >
+                                                 held * cur.per_token + take * own.per_token + kOpenCost) {
+                                close();
+                                held = 0;
+                                continue;
+                            }
+                        } else {
+                            take = std::min<int64_t>(left, limit(own.tasks));
+                        }
+                        node_range(u, done, (int32_t)take, u_lo, u_hi);
+                        held += take;
+                        c_lo = lo;
+                        c_hi = hi;
+                        done += (int32_t)take;
+                    }
+                }
+                break;
+            }
             default: return DEFT_EINVAL;
         }
         if (flat > INT32_MAX || P->seg_len.size() > (size_t)INT32_MAX / 2) return DEFT_EINVAL;
         P->n_flat = (int32_t)flat;
         P->chunk_seg_ptr.push_back(P->n_segs());  // closes the last chunk; {0} when there is none
         const int32_t m = (int32_t)P->chunk_seg_ptr.size() - 1;
+        // The kernels expand a chunk of several pieces into a per-token table of at most DEFT_MAX_CHUNK entries; a
+        // single piece needs none and may have any length.  Only DEFT_SPLIT_NODE can produce a longer chunk of
+        // several pieces (a long node scattered over pages): such a plan could not be decoded and is refused here.
+        for (int32_t c = 0; c < m; ++c) {
+            const int32_t s0 = P->chunk_seg_ptr[c], s1 = P->chunk_seg_ptr[c + 1];
+            if (s1 - s0 < 2) continue;
+            int64_t len = 0;
+            for (int32_t s = s0; s < s1; ++s) len += P->seg_len[s];
+            if (len > DEFT_MAX_CHUNK) return DEFT_EINVAL;
+        }
 
         // ---- KV-guided grouping: the queries of each chunk, and the slots of their partials ----
         P->chunk_qlo.resize(m);
@@ -386,9 +452,12 @@ extern "C" int deft_plan_paged(const int32_t *node_page_ptr, const int32_t *page
 // gets the same number of bytes, i.e. when there are about 512 equal tasks.  The estimate weighs each
 // reached node's tokens by the number of 128-row tasks its own query group needs.
 extern "C" int32_t deft_suggest_chunk_size(const int32_t *node_tok_len, const int32_t *node_parent, int32_t n_nodes,
-                                           const int32_t *query_node, int32_t nq, int32_t Hq, int32_t Hkv) {
+                                           const int32_t *query_node, int32_t nq, int32_t Hq, int32_t Hkv,
+                                           uint32_t flags) {
     if (!node_tok_len || !node_parent || n_nodes < 1 || nq < 0 || (nq > 0 && !query_node)) return DEFT_EINVAL;
     if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return DEFT_EINVAL;
+    const uint32_t mode = flags & 0xffu;
+    if (mode > DEFT_SPLIT_BALANCED) return DEFT_EINVAL;
     try {
         for (int32_t u = 0; u < n_nodes; ++u)
             if (node_parent[u] < -1 || node_parent[u] >= n_nodes || node_parent[u] == u || node_tok_len[u] < 0)
@@ -404,13 +473,22 @@ extern "C" int32_t deft_suggest_chunk_size(const int32_t *node_tok_len, const in
             if (p >= 0) sub[p] += sub[u];
         }
         const int64_t G = Hq / Hkv;
-        long double task_tokens = 0;
+        long double task_tokens = 0, reached_tokens = 0;
         bool wide = false;  // some tokens are shared by more rows than one task takes
         for (int32_t u = 0; u < n_nodes; ++u) {
             if (sub[u] == 0) continue;
             const int64_t row_groups = (sub[u] * G + 127) / 128;
             task_tokens += (long double)node_tok_len[u] * (long double)row_groups;
+            reached_tokens += (long double)node_tok_len[u];
             if (row_groups > 1 && node_tok_len[u] > 0) wide = true;
+        }
+        if (mode == DEFT_SPLIT_BALANCED) {
+            // The balanced split stretches the chunks of wide groups by itself, so the size asked for is that of
+            // a narrow chunk: one dispatch round of them if the tree is small, 768 tokens otherwise (measured on
+            // the reasoning and long-context trees: two rounds of 768-token tasks beat one round of longer ones,
+            // because the long tasks of the wide groups then share compute units with streaming narrow ones).
+            int64_t chunk = ((int64_t)(reached_tokens * Hkv / 512.0L) + 127) / 128 * 128;
+            return (int32_t)std::max<int64_t>(128, std::min<int64_t>(768, chunk));
         }
         const long double per_task = task_tokens * Hkv / 512.0L;
         // a multiple of 128 tokens = 4 waves x 32-token blocks, so a token-split task gives every wave the same work.

@@ -28,10 +28,15 @@ PRECISE_BELOW = 1024     # tokens on a path below which the library uses two-ter
 U_PRECISE = 2.0 ** -13   # bound on the relative error of a two-term weight and the fp32 sums, with margin
 
 
+def mode_flags(mode, G):
+    """deft_plan flags of a split; the balanced one is told how many query heads share a KV head"""
+    return binding.SPLIT_MODES[mode] | (binding.rows_per_query(G) if mode == "balanced" else 0)
+
+
 def run_gpu(t, Q, K, V, chunk_size=0, out_dtype=torch.bfloat16, scale=0.0, mode="flatten"):
     dev = torch.device("cuda:0")
     plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, chunk_size,
-                             binding.SPLIT_MODES[mode])
+                             mode_flags(mode, t.Hq // t.Hkv))
     q, k, v = Q.to(dev), K.to(dev), V.to(dev)
     o = binding.deft_tree_attn_decode(plan, q, k, v, out_dtype=out_dtype, scale=scale)
     torch.cuda.synchronize()
@@ -108,13 +113,15 @@ def test_benchmark_configs_match_oracle(cfg):
         assert np.array_equal(view[key], want[key]), key
 
 
+@pytest.mark.parametrize("mode", ["flatten", "balanced"])
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5])
-def test_benchmark_configs_at_the_chunk_size_bench_uses(cfg):
+def test_benchmark_configs_at_the_chunk_size_bench_uses(cfg, mode):
     t = wl.make_config(cfg)
-    chunk = binding.deft_suggest_chunk_size(t.node_tok_len, t.node_parent, t.query_node, t.Hq, t.Hkv)
-    print(f"\n  config {cfg} at suggested chunk {chunk}", flush=True)
+    chunk = binding.deft_suggest_chunk_size(t.node_tok_len, t.node_parent, t.query_node, t.Hq, t.Hkv,
+                                            binding.SPLIT_MODES[mode])
+    print(f"\n  config {cfg}, {mode} split at the suggested chunk size {chunk}", flush=True)
     Q, K, V = wl.make_qkv(t)
-    got, _ = run_gpu(t, Q, K, V, chunk_size=chunk)
+    got, _ = run_gpu(t, Q, K, V, chunk_size=chunk, mode=mode)
     check(got, reference(t, Q, K, V), strict=True)
 
 
@@ -160,9 +167,9 @@ def test_stage1_partials_match_algorithm4_and_stage2_completes_them():
           two_term=all_paths_short(t))
 
 
-@pytest.mark.parametrize("mode", ["node", "node_chunk", "query"])
+@pytest.mark.parametrize("mode", ["node", "node_chunk", "query", "balanced"])
 def test_other_partitioning_strategies_give_the_same_attention(mode):
-    # DeFT-Node, DeFT-Node-Chunk and Q-guided grouping run on the same kernels through the plan
+    # DeFT-Node, DeFT-Node-Chunk, Q-guided grouping and the tokens x rows split run on the same kernels through the plan
     for cfg in (1, 2, 3):
         t = wl.make_config(cfg)
         print(f"\n  config {cfg} mode {mode}", flush=True)
@@ -435,11 +442,11 @@ def test_randomised_sweep_of_shapes_strategies_and_storage():
             kp = wl.scatter_to_pool(K, row_of, npool * page, 1).cuda()
             vp = wl.scatter_to_pool(V, row_of, npool * page, 2).cuda()
             plan = binding.deft_plan_paged(pp, pg, page, npool, t.node_tok_len, t.node_parent, t.query_node, chunk,
-                                           binding.SPLIT_MODES[mode])
+                                           mode_flags(mode, G))
             got = binding.deft_tree_attn_decode(plan, Q.cuda(), kp, vp, out_dtype=torch.float32)
         else:
             plan = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, chunk,
-                                     binding.SPLIT_MODES[mode])
+                                     mode_flags(mode, G))
             got = binding.deft_tree_attn_decode(plan, Q.cuda(), K.cuda(), V.cuda(), out_dtype=torch.float32)
         torch.cuda.synchronize()
         got = got.cpu().numpy().astype(np.float64)

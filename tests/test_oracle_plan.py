@@ -19,14 +19,14 @@ import pytest
 
 import oracle
 from oracle import deft_flatten
-from oracle.plan import PlanError, flatten_plan
+from oracle.plan import PlanError, _balanced_weight, flatten_plan
 from paper_2404_00242_amd import workloads as wl
 
 GOLDEN = sorted(glob.glob(os.path.join(os.path.dirname(__file__), "golden", "plan_*.json")))
 
 
-def plan_of(t, B=128, mode="flatten"):
-    return flatten_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B, mode)
+def plan_of(t, B=128, mode="flatten", G=1):
+    return flatten_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B, mode, G)
 
 
 def path_pairs(t):
@@ -67,6 +67,8 @@ def check_invariants(t, p, B, mode="flatten"):
         n = int(p["seg_len"][p["chunk_seg_ptr"][ch]:p["chunk_seg_ptr"][ch + 1]].sum())
         if mode == "flatten":
             assert n == (B if ch < m - 1 else p["n_flat"] - B * (m - 1))  # even blocks, short tail
+        elif mode == "balanced":
+            assert 0 < n <= 4 * B
         elif mode != "node":
             assert 0 < n <= B
         assert p["chunk_seg_ptr"][ch + 1] > p["chunk_seg_ptr"][ch]
@@ -214,6 +216,65 @@ def test_other_partitioning_strategies_cover_the_same_pairs(seed, mode):
         Q, K, V = (x.float().numpy() for x in wl.make_qkv(t))
         ref = oracle.tree_attention(Q, K, V, t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node)
         np.testing.assert_allclose(deft_flatten.attention_by_plan(p, Q, K, V), ref, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_balanced_split_covers_the_same_pairs_and_obeys_its_cost_rule(seed):
+    """The tokens x rows variant of the flattened split: same depth-first order and the same (query, token) pairs
+    as every other strategy; no chunk longer than min(tasks, 4) * S_t for its group's number of tasks; no chunk
+    dearer than its pieces apart plus one opening cost per join (what the greedy rule guarantees); Algorithm 4 on
+    it gives the definition."""
+    G = [1, 2, 4, 8][seed % 4]
+    t = wl.random_tree(800 + seed, n_nodes=3 + seed, max_len=120, nq=2 + 3 * seed, Hq=2 * G, Hkv=2, d=8,
+                       n_roots=1 + seed % 2)
+    B = 32
+    p = plan_of(t, B, "balanced", G)
+    check_invariants(t, p, B, "balanced")
+    f = plan_of(t, B, "flatten")
+    assert p["n_flat"] == f["n_flat"]
+    # same tokens in the same (depth-first) order as the equal-token split, only the cuts differ
+    def rows_in_order(q):
+        return [r for s in range(q["n_segs"]) for r in range(int(q["seg_tok_begin"][s]), int(q["seg_tok_begin"][s] + q["seg_len"][s]))]
+    assert rows_in_order(p) == rows_in_order(f)
+    for c in range(p["n_chunks"]):
+        segs = range(int(p["chunk_seg_ptr"][c]), int(p["chunk_seg_ptr"][c + 1]))
+        w, tasks = _balanced_weight(int(p["chunk_qhi"][c] - p["chunk_qlo"][c]), G)
+        n = int(sum(p["seg_len"][s] for s in segs))
+        assert n <= B * min(tasks, 4)
+        apart, joins, last = 0, -1, None
+        for s in segs:
+            apart += int(p["seg_len"][s]) * _balanced_weight(int(p["seg_qhi"][s] - p["seg_qlo"][s]), G)[0]
+            if int(p["seg_node"][s]) != last:
+                joins, last = joins + 1, int(p["seg_node"][s])
+        assert n * w <= apart + 192 * joins
+    if seed < 6:
+        Q, K, V = (x.float().numpy() for x in wl.make_qkv(t))
+        ref = oracle.tree_attention(Q, K, V, t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node)
+        np.testing.assert_allclose(deft_flatten.attention_by_plan(p, Q, K, V), ref, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_balanced_split_is_the_flattened_split_when_every_group_costs_the_same(seed):
+    # at most 16 rows everywhere: one tile, one task, one weight -> joining never costs, limits are S_t: Remark 3.1's cuts
+    t = wl.random_tree(850 + seed, n_nodes=2 + 2 * seed, max_len=90, nq=1 + seed % 8, n_roots=1 + seed % 2)
+    for B in (32, 64):
+        a, b = plan_of(t, B, "balanced", 2), plan_of(t, B, "flatten")
+        for key in b:
+            assert np.array_equal(a[key], b[key]), key
+
+
+def test_balanced_split_on_the_long_context_tree():
+    # config 5 at S_t = 768: the 32768-token root is shared by 480 rows = 30 tiles = 4 tasks, so it is cut every
+    # 4 * 768 tokens: ceil(32768 / 3072) = 11 chunks with 120 slots each; no other node is that wide
+    t = wl.make_config(5)
+    p = plan_of(t, 768, "balanced", 4)
+    root = [c for c in range(p["n_chunks"]) if p["chunk_qhi"][c] - p["chunk_qlo"][c] == 120]
+    assert len(root) == 11
+    lens = [int(p["seg_len"][p["chunk_seg_ptr"][c]:p["chunk_seg_ptr"][c + 1]].sum()) for c in root]
+    assert lens == [3072] * 10 + [32768 - 30720]
+    others = [c for c in range(p["n_chunks"]) if c not in root]
+    assert max(int(p["chunk_qhi"][c] - p["chunk_qlo"][c]) for c in others) <= 8
+    assert p["n_flat"] == t.ntok
 
 
 def test_share_factor_of_the_few_shot_tree():

@@ -17,10 +17,10 @@ ARRAYS = ("q_order", "node_q_lo", "node_q_hi", "chunk_seg_ptr", "seg_tok_begin",
 SCALARS = ("chunk_size", "n_nodes", "nq", "n_flat", "n_chunks", "n_segs", "n_slots")
 
 
-def assert_same_plan(t, B, mode="flatten"):
-    ref = flatten_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B, mode)
+def assert_same_plan(t, B, mode="flatten", G=1):
+    ref = flatten_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B, mode, G)
     got = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, B,
-                            binding.SPLIT_MODES[mode]).view()
+                            binding.SPLIT_MODES[mode] | (binding.rows_per_query(G) if G > 1 else 0)).view()
     for s in SCALARS:
         assert got[s] == ref[s], s
     assert got["n_mask_words"] == len(ref["seg_mask"])
@@ -85,8 +85,9 @@ def test_wide_group_masks():
 def test_hand_derived_fixtures(path):
     g = json.load(open(path))
     i = g["input"]
+    flags = binding.SPLIT_MODES[i.get("mode", "flatten")] | binding.rows_per_query(i.get("rows_per_query", 0))
     got = binding.deft_plan(i["node_tok_begin"], i["node_tok_len"], i["node_parent"], i["query_node"], i["ntok"],
-                            i["chunk_size"]).view()
+                            i["chunk_size"], flags).view()
     for key, want in g["expect"].items():
         assert (got[key].tolist() if isinstance(want, list) else got[key]) == want, key
 
@@ -168,6 +169,30 @@ def test_other_partitioning_strategies(mode):
         assert_same_plan(wl.make_config(cfg), 128, mode)
     with pytest.raises(binding.DeftError):
         binding.deft_plan([0], [4], [-1], [0], 4, 32, 7)       # unknown strategy
+    with pytest.raises(binding.DeftError):
+        binding.deft_suggest_chunk_size([4], [-1], [0], 4, 2, 7)
+
+
+def test_balanced_split_matches_the_oracle():
+    # the tokens x rows split needs the number of query heads per KV head; wide and narrow groups, several sizes
+    for seed in range(60):
+        G = [1, 2, 4, 8, 5][seed % 5]
+        t = wl.random_tree(900 + seed, n_nodes=1 + seed % 23, max_len=150, nq=(seed * 3) % 41, n_roots=1 + seed % 3,
+                           zero_len_prob=0.1)
+        for B in (32, 64, 256):
+            assert_same_plan(t, B, "balanced", G)
+    for cfg in (1, 2, 3, 4, 5):
+        t = wl.make_config(cfg)
+        for B in (128, 768):
+            assert_same_plan(t, B, "balanced", t.Hq // t.Hkv)
+    # a very wide, very long node: chunks stop at DEFT_MAX_CHUNK tokens whatever the stretch
+    t = wl._finish("wide", [20000, 8], [-1, 0], [1] * 200, 8, 2, 128, 3)
+    assert_same_plan(t, 2048, "balanced", 4)
+    v = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok, 2048,
+                          binding.DEFT_SPLIT_BALANCED | binding.rows_per_query(4)).view()
+    assert int(v["seg_len"].max()) == 4096
+    with pytest.raises(binding.DeftError):   # bits outside the mode, the weights flag and the rows field
+        binding.deft_plan([0], [4], [-1], [0], 4, 32, binding.DEFT_SPLIT_BALANCED | 0x200)
 
 
 def test_corrupted_trees_are_accepted_or_refused_exactly_as_by_the_oracle():
