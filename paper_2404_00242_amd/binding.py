@@ -180,20 +180,37 @@ class Plan:
         return int(load_library().deft_workspace_bytes(self._h, Hq, Hkv, d))
 
     def image(self, Hq: int, Hkv: int, device, stream=None):
-        """Device image for this Hq/Hkv ratio, uploaded on first use (memory comes from torch)."""
+        """Device image for this Hq/Hkv ratio, uploaded on first use (memory comes from torch).
+
+        deft_plan_upload only enqueues the copy on the stream of that first call.  An event recorded behind it
+        is kept with the image, and a later call on another stream makes that stream wait for the event, so
+        that no kernel can read the image before the copy has landed."""
         import torch
 
         device = torch.device(device)
+        if stream is None:
+            stream = torch.cuda.current_stream(device)
         key = (Hq // Hkv, device.index)
-        img = self._images.get(key)
-        if img is None:
+        entry = self._images.get(key)
+        if entry is None:
             nbytes = self.device_bytes(Hq, Hkv)
             if nbytes == 0:
                 raise DeftError(-1, "deft_plan_device_bytes: invalid Hq/Hkv")
             img = torch.empty(nbytes, dtype=torch.uint8, device=device)
             st = _stream_ptr(stream, device)
             _check(load_library().deft_plan_upload(self._h, Hq, Hkv, img.data_ptr(), nbytes, st), "deft_plan_upload")
-            self._images[key] = img
+            uploaded = None
+            if hasattr(stream, "record_event"):
+                uploaded = torch.cuda.Event()
+                stream.record_event(uploaded)
+            entry = (img, uploaded, getattr(stream, "cuda_stream", stream))
+            self._images[key] = entry
+        img, uploaded, on = entry
+        if uploaded is not None:
+            if uploaded.query():  # the copy has landed: nothing to order any more
+                self._images[key] = (img, None, on)
+            elif getattr(stream, "cuda_stream", stream) != on and hasattr(stream, "wait_event"):
+                stream.wait_event(uploaded)
         return img
 
     def workspace(self, Hq: int, Hkv: int, d: int, device):

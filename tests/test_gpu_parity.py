@@ -264,6 +264,22 @@ def test_repeated_calls_and_plan_reuse_are_deterministic():
         c = binding.deft_tree_attn_decode(plan, q, k, v, stream=s)
     s.synchronize()
     assert torch.equal(a, c)
+    # also when the image's upload is still queued on another stream: the first call (which uploads) sits behind
+    # a long fill on the current stream, the second call comes on a side stream that waits for nothing but the
+    # workspace's owner; the binding orders it behind the upload
+    plan3 = binding.deft_plan(t.node_tok_begin, t.node_tok_len, t.node_parent, t.query_node, t.ntok)
+    big = torch.empty(1 << 28, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        big.add_(1)
+    plan3.image(t.Hq, t.Hkv, dev)                      # upload enqueued behind the fills
+    s2 = torch.cuda.Stream()
+    ws2 = torch.empty(plan3.workspace_bytes(t.Hq, t.Hkv, t.d), dtype=torch.uint8, device=dev)
+    with torch.cuda.stream(s2):
+        e = binding.deft_tree_attn_decode(plan3, q, k, v, workspace=ws2, stream=s2)
+    s2.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(a, e)
 
 
 def test_error_paths_do_not_launch():

@@ -52,13 +52,14 @@ def test_oracle_pages_in_pool_order_are_a_contiguous_cache():
 
 
 @pytest.mark.parametrize("seed", range(10))
-@pytest.mark.parametrize("mode", ["flatten", "node_chunk", "query"])
+@pytest.mark.parametrize("mode", ["flatten", "node", "node_chunk", "query", "balanced"])
 def test_paged_plan_covers_every_pair_once_and_matches_the_planner(seed, mode):
     page_size = [1, 4, 16, 16, 5][seed % 5]
     t = wl.random_tree(600 + seed, n_nodes=2 + seed, max_len=60, nq=1 + 2 * seed, n_roots=1 + seed % 2)
     pp, pg, npool, row_of = wl.to_paged(t, page_size, seed=seed)
     B = 32
-    ref = flatten_plan_paged(pp, pg, page_size, npool, t.node_tok_len, t.node_parent, t.query_node, B, mode)
+    G = 4 if mode == "balanced" else 1
+    ref = flatten_plan_paged(pp, pg, page_size, npool, t.node_tok_len, t.node_parent, t.query_node, B, mode, G)
     # coverage against an independent walk: (query, pool row) pairs, each once
     want = Counter()
     for j, u in enumerate(t.query_node):
@@ -78,9 +79,31 @@ def test_paged_plan_covers_every_pair_once_and_matches_the_planner(seed, mode):
         assert ref["n_chunks"] == -(-ref["n_flat"] // B)
     # the C++ planner gives the same arrays
     view = binding.deft_plan_paged(pp, pg, page_size, npool, t.node_tok_len, t.node_parent, t.query_node, B,
-                                   binding.SPLIT_MODES[mode]).view()
+                                   binding.SPLIT_MODES[mode] | (binding.rows_per_query(G) if G > 1 else 0)).view()
     for a in ARRAYS:
         assert np.array_equal(view[a], ref[a]), a
+
+
+def test_a_node_too_long_for_one_chunk_and_scattered_over_pages_is_refused_at_plan_time():
+    """DeFT-Node makes one chunk per node whatever its length.  A chunk of several pieces is expanded by the
+    kernels into a table of at most DEFT_MAX_CHUNK = 4096 entries, so a longer node whose pages are not one run
+    cannot be decoded: the planner says so (DEFT_EINVAL) instead of handing out a plan that fails at launch.
+    The same node in one run of pages, or cut by any other split, is fine."""
+    P, n = 16, 5000
+    pages = -(-n // P)
+    ptr = [0, pages, pages + 1]
+    scattered = list(range(pages - 1, -1, -1)) + [pages]     # the node's pages in reverse pool order
+    in_order = list(range(pages + 1))
+    args = dict(page_size=P, n_pool_pages=pages + 1, node_tok_len=[n, 3], node_parent=[-1, 0], query_node=[1, 1])
+    with pytest.raises(binding.DeftError) as e:
+        binding.deft_plan_paged(ptr, scattered, chunk_size=128, flags=binding.DEFT_SPLIT_NODE, **args)
+    assert e.value.status == -1
+    v = binding.deft_plan_paged(ptr, in_order, chunk_size=128, flags=binding.DEFT_SPLIT_NODE, **args).view()
+    assert v["n_chunks"] == 2 and int(v["seg_len"].max()) == n
+    for mode in ("flatten", "node_chunk", "balanced", "query"):
+        v = binding.deft_plan_paged(ptr, scattered, chunk_size=4096, flags=binding.SPLIT_MODES[mode], **args).view()
+        lens = [int(v["seg_len"][v["chunk_seg_ptr"][c]:v["chunk_seg_ptr"][c + 1]].sum()) for c in range(v["n_chunks"])]
+        assert max(lens) <= 4096
 
 
 def test_paged_planner_rejects_bad_page_tables():
