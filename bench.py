@@ -295,6 +295,17 @@ def measure(cfg, args, lib, dev, with_oracle, cpu_seconds):
         w.prepare()
     plan_us = (time.perf_counter() - tp0) * 1e5
     torch.cuda.synchronize()
+    # and of deft_plan_update from the previous plan when the tree has not changed at all (its best case: every
+    # chunk but the last is taken over; a decode iteration that grows every leaf saves far less)
+    update_us = None
+    if w.P == 0:
+        hs = [ctypes.c_void_p() for _ in range(10)]
+        tu0 = time.perf_counter()
+        for h_new in hs:
+            w.check(lib.deft_plan_update(w.plans[-1], w.nbp, w.nlp, w.parp, tree.n_nodes, w.qnp, tree.nq, tree.ntok,
+                                         w.chunk, w.mode_flag, ctypes.byref(h_new)), "deft_plan_update")
+        update_us = (time.perf_counter() - tu0) * 1e5
+        w.plans.extend(hs)
 
     s1, s2 = w.stage_times(max(args.steps, 1))
     s1_us, s2_us = float(np.mean(s1)), float(np.mean(s2))
@@ -347,6 +358,7 @@ def measure(cfg, args, lib, dev, with_oracle, cpu_seconds):
                                  ("stage 1 alone meets it, the whole call does not" if achieved / HBM_PEAK_GBS >= TARGET_FRAC
                                   else "missed"))),
         "plan_plus_upload_us": round(plan_us, 1),
+        "plan_update_unchanged_tree_us": None if update_us is None else round(update_us, 1),
     }
     detail = {
         "tree": tree, "view": w.view, "step_s": step_s, "us_per_call": us_per_call, "per_step_us": per_step_us,

@@ -180,6 +180,27 @@ int deft_plan_paged(const int32_t *node_page_ptr, const int32_t *page_ids, int32
                     deft_plan_t **out_plan);
 
 /*
+ * The preparation phase for a tree that has changed since `prev` was planned.  During decoding the branch
+ * controller and the KV manager change the tree between two calls of the attention kernel (Appendix A.1:
+ * every live leaf gains a token, now and then a leaf forks or a branch is pruned), and the plan has to
+ * follow every iteration (Fig. 9 measures latency per iteration).  The arguments after `prev` are those of
+ * deft_plan / deft_plan_paged and describe the whole new tree; the result is exactly the plan those calls
+ * would give for it (same arrays, same errors).  `prev` only saves work: when the parents and the query map
+ * are unchanged, the depth-first order and the renumbering of the queries are taken over, and when split and
+ * chunk size are unchanged as well, so is every chunk that lies in front of the first node whose tokens
+ * differ, together with the chunk behind it if that one also starts in front of the change.  Anything may have
+ * changed; in the worst case the call does what deft_plan does.  prev may be NULL (then it is deft_plan), is
+ * not modified, and both plans stay valid and independent.
+ */
+int deft_plan_update(const deft_plan_t *prev, const int32_t *node_tok_begin, const int32_t *node_tok_len,
+                     const int32_t *node_parent, int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t ntok,
+                     int32_t chunk_size, uint32_t flags, deft_plan_t **out_plan);
+int deft_plan_paged_update(const deft_plan_t *prev, const int32_t *node_page_ptr, const int32_t *page_ids,
+                           int32_t page_size, int32_t n_pool_pages, const int32_t *node_tok_len,
+                           const int32_t *node_parent, int32_t n_nodes, const int32_t *query_node, int32_t nq,
+                           int32_t chunk_size, uint32_t flags, deft_plan_t **out_plan);
+
+/*
  * A chunk size S_t suited to this tree on an MI355X (the paper leaves S_t as a tuning knob, Fig. 11).
  * flags names the split the size is for (a DEFT_SPLIT_* / DEFT_GROUP_QUERY value; other bits are ignored).
  * For DEFT_SPLIT_BALANCED: the multiple of 128 that gives about one stage-1 task per resident workgroup slot

@@ -35,7 +35,7 @@ def rows_per_query(g: int) -> int:
     return (int(g) & 0xFFF) << 16
 
 EXPORTS = (
-    "deft_plan", "deft_plan_paged", "deft_suggest_chunk_size", "deft_plan_view", "deft_plan_device_bytes", "deft_plan_upload", "deft_workspace_bytes",
+    "deft_plan", "deft_plan_paged", "deft_plan_update", "deft_plan_paged_update", "deft_suggest_chunk_size", "deft_plan_view", "deft_plan_device_bytes", "deft_plan_upload", "deft_workspace_bytes",
     "deft_tree_attn_decode", "deft_tree_attn_decode_static", "deft_stage1_partial_attention", "deft_stage2_global_reduction",
     "deft_hbm_read_probe", "deft_plan_destroy", "deft_strerror", "deft_last_hip_error",
 )
@@ -95,6 +95,10 @@ def load_library():
     lib.deft_plan_paged.restype = ctypes.c_int
     lib.deft_plan_paged.argtypes = [_i32p, _i32p, c32, c32, _i32p, _i32p, c32, _i32p, c32, c32, ctypes.c_uint32,
                                     ctypes.POINTER(vp)]
+    lib.deft_plan_update.restype = ctypes.c_int
+    lib.deft_plan_update.argtypes = [vp] + lib.deft_plan.argtypes
+    lib.deft_plan_paged_update.restype = ctypes.c_int
+    lib.deft_plan_paged_update.argtypes = [vp] + lib.deft_plan_paged.argtypes
     lib.deft_suggest_chunk_size.restype = ctypes.c_int32
     lib.deft_suggest_chunk_size.argtypes = [_i32p, _i32p, c32, _i32p, c32, c32, c32, ctypes.c_uint32]
     lib.deft_plan_view.restype = ctypes.c_int
@@ -249,33 +253,40 @@ def deft_suggest_chunk_size(node_tok_len, node_parent, query_node, Hq: int, Hkv:
 
 
 def deft_plan(node_tok_begin, node_tok_len, node_parent, query_node, ntok: int, chunk_size: int = 0,
-              flags: int = 0) -> Plan:
-    """QKV Preparation Phase (Algorithm 3): builds the flattened chunk / bit-mask plan on the host."""
+              flags: int = 0, prev: "Plan | None" = None) -> Plan:
+    """QKV Preparation Phase (Algorithm 3): builds the flattened chunk / bit-mask plan on the host.
+    prev: the plan of an earlier version of the tree (deft_plan_update: same result, less work)."""
     lib = load_library()
     nb, nl, par, qn = _i32(node_tok_begin), _i32(node_tok_len), _i32(node_parent), _i32(query_node)
     if not (nb.size == nl.size == par.size):
         raise DeftError(-1, "deft_plan: node table columns differ in length")
     out = ctypes.c_void_p()
     qptr = qn.ctypes.data_as(_i32p) if qn.size else None
-    rc = lib.deft_plan(nb.ctypes.data_as(_i32p), nl.ctypes.data_as(_i32p), par.ctypes.data_as(_i32p), nb.size,
-                       qptr, qn.size, int(ntok), int(chunk_size), int(flags), ctypes.byref(out))
-    _check(rc, "deft_plan")
+    args = (nb.ctypes.data_as(_i32p), nl.ctypes.data_as(_i32p), par.ctypes.data_as(_i32p), nb.size,
+            qptr, qn.size, int(ntok), int(chunk_size), int(flags), ctypes.byref(out))
+    if prev is None:
+        _check(lib.deft_plan(*args), "deft_plan")
+    else:
+        _check(lib.deft_plan_update(prev.handle, *args), "deft_plan_update")
     return Plan(out)
 
 
 def deft_plan_paged(node_page_ptr, page_ids, page_size: int, n_pool_pages: int, node_tok_len, node_parent,
-                    query_node, chunk_size: int = 0, flags: int = 0) -> Plan:
-    """QKV Preparation Phase over a paged KV pool (K/V are [n_pool_pages * page_size, Hkv, d])."""
+                    query_node, chunk_size: int = 0, flags: int = 0, prev: "Plan | None" = None) -> Plan:
+    """QKV Preparation Phase over a paged KV pool (K/V are [n_pool_pages * page_size, Hkv, d]).
+    prev: the plan of an earlier version of the tree (deft_plan_paged_update: same result, less work)."""
     lib = load_library()
     pp, pg, nl, par, qn = (_i32(x) for x in (node_page_ptr, page_ids, node_tok_len, node_parent, query_node))
     if not (nl.size == par.size == pp.size - 1):
         raise DeftError(-1, "deft_plan_paged: node table columns differ in length")
     out = ctypes.c_void_p()
-    rc = lib.deft_plan_paged(pp.ctypes.data_as(_i32p), pg.ctypes.data_as(_i32p) if pg.size else None, int(page_size),
-                             int(n_pool_pages), nl.ctypes.data_as(_i32p), par.ctypes.data_as(_i32p), nl.size,
-                             qn.ctypes.data_as(_i32p) if qn.size else None, qn.size, int(chunk_size), int(flags),
-                             ctypes.byref(out))
-    _check(rc, "deft_plan_paged")
+    args = (pp.ctypes.data_as(_i32p), pg.ctypes.data_as(_i32p) if pg.size else None, int(page_size),
+            int(n_pool_pages), nl.ctypes.data_as(_i32p), par.ctypes.data_as(_i32p), nl.size,
+            qn.ctypes.data_as(_i32p) if qn.size else None, qn.size, int(chunk_size), int(flags), ctypes.byref(out))
+    if prev is None:
+        _check(lib.deft_plan_paged(*args), "deft_plan_paged")
+    else:
+        _check(lib.deft_plan_paged_update(prev.handle, *args), "deft_plan_paged_update")
     return Plan(out)
 
 

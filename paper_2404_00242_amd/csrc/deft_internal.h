@@ -62,6 +62,16 @@ struct deft_plan_s {
     uint32_t mode = 0;  // DEFT_SPLIT_* / DEFT_GROUP_QUERY
     bool precise_all = false;  // DEFT_PRECISE_WEIGHTS was given
     std::vector<int32_t> q_path_len;  // tokens on the whole path of plan position p (saturating)
+
+    // What the plan was built from and where its chunks start, kept so that deft_plan_update can tell what a new
+    // tree has in common with this one and take over the chunks in front of the first change.
+    uint32_t flags = 0;
+    std::vector<int32_t> in_parent, in_query_node, in_tok_len, in_ext_ptr, in_ext_begin, in_ext_len;
+    std::vector<int32_t> pre;              // depth-first order of the nodes
+    std::vector<int32_t> chunk_first_i;    // position in `pre` of the node of a chunk's first piece,
+    std::vector<int32_t> chunk_first_done; // tokens of that node that lie in earlier chunks,
+    std::vector<int32_t> chunk_last_i;     // position in `pre` of the node of its last piece,
+    std::vector<int64_t> chunk_flat_begin; // flattened position of its first token
     std::vector<int32_t> q_order, node_q_lo, node_q_hi;
     std::vector<int32_t> chunk_seg_ptr, seg_tok_begin, seg_len, seg_qlo, seg_qhi, seg_node;
     std::vector<int32_t> chunk_qlo, chunk_qhi, chunk_slot_base;

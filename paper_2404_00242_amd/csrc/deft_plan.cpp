@@ -62,9 +62,13 @@ struct NodeExtents {
     std::vector<int32_t> ptr, begin, len;
 };
 
+// prev: a plan of an earlier version of the tree, or null.  Whatever the new tree shares with it is taken over
+// instead of being recomputed: the depth-first order and the renumbering of the queries when parents and the
+// query map are the same, and every chunk in front of the first node whose tokens differ when the split and
+// the chunk size are the same too.  The result is the plan a call without prev gives.
 int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t *node_parent, int32_t n_nodes,
               const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size, uint32_t flags,
-              deft_plan_t **out_plan) {
+              deft_plan_t **out_plan, const deft_plan_t *prev = nullptr) {
     if (n_nodes < 1 || nq < 0 || ntok < 0) return DEFT_EINVAL;
     const uint32_t mode = flags & 0xffu;
     const int32_t rows_per_query = (int32_t)((flags >> 16) & 0xfffu);  // DEFT_ROWS_PER_QUERY(g), 0 = not given
@@ -78,6 +82,7 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
         const int32_t n = n_nodes;
         // ---- validation -------------------------------------------------------------------
         std::vector<Range> spans;
+        spans.reserve(ext.len.size());
         for (int32_t u = 0; u < n; ++u) {
             int32_t p = node_parent[u];
             if (p < -1 || p >= n || p == u) return DEFT_EINVAL;
@@ -91,14 +96,19 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
             }
             if (total != node_tok_len[u]) return DEFT_EINVAL;
         }
-        std::sort(spans.begin(), spans.end(), [](const Range &a, const Range &b) { return a.begin < b.begin; });
+        // (a cache that hands out rows in node order, the usual case, is sorted already)
+        auto by_begin = [](const Range &a, const Range &b) { return a.begin < b.begin; };
+        if (!std::is_sorted(spans.begin(), spans.end(), by_begin)) std::sort(spans.begin(), spans.end(), by_begin);
         for (size_t i = 1; i < spans.size(); ++i)
             if (spans[i].begin < spans[i - 1].end) return DEFT_EINVAL;
         for (int32_t j = 0; j < nq; ++j)
             if (query_node[j] < 0 || query_node[j] >= n) return DEFT_EINVAL;
 
-        std::vector<int32_t> pre, first_child, next_sibling;
-        if (!preorder(node_parent, n, pre, first_child, next_sibling)) return DEFT_EINVAL;  // cycle
+        // same parents and same query map as prev: same depth-first order, same query intervals
+        const bool same_topology =
+            prev && prev->n_nodes == n && prev->nq == nq &&
+            std::memcmp(prev->in_parent.data(), node_parent, (size_t)n * sizeof(int32_t)) == 0 &&
+            (nq == 0 || std::memcmp(prev->in_query_node.data(), query_node, (size_t)nq * sizeof(int32_t)) == 0);
 
         deft_plan_t *P = new deft_plan_s();
         std::unique_ptr<deft_plan_t> guard(P);
@@ -108,10 +118,30 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
         P->ntok = ntok;
         P->mode = mode;
         P->precise_all = (flags & DEFT_PRECISE_WEIGHTS) != 0;
+        P->flags = flags;
+        P->in_parent.assign(node_parent, node_parent + n);
+        P->in_query_node.assign(query_node, query_node + nq);
+        P->in_tok_len.assign(node_tok_len, node_tok_len + n);
+        P->in_ext_ptr = ext.ptr;
+        P->in_ext_begin = ext.begin;
+        P->in_ext_len = ext.len;
+
+        std::vector<int32_t> &pre = P->pre;
+        if (same_topology) {
+            pre = prev->pre;
+        } else {
+            std::vector<int32_t> first_child, next_sibling;
+            if (!preorder(node_parent, n, pre, first_child, next_sibling)) return DEFT_EINVAL;  // cycle
+        }
 
         // ---- depth-first renumbering of the queries ------------------------------------------
         // A node's own queries come first, then its subtrees, so the queries whose path contains u
         // are one interval.  q_hi[u] = q_lo[u] + (number of queries in u's subtree).
+        if (same_topology) {
+            P->node_q_lo = prev->node_q_lo;
+            P->node_q_hi = prev->node_q_hi;
+            P->q_order = prev->q_order;
+        } else {
         std::vector<int32_t> own(n, 0), sub(n, 0);
         for (int32_t j = 0; j < nq; ++j) ++own[query_node[j]];
         sub = own;
@@ -139,6 +169,7 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
             std::vector<int32_t> cursor = own_begin;  // next free plan position among u's own queries
             for (int32_t j = 0; j < nq; ++j) P->q_order[cursor[query_node[j]]++] = j;
         }
+        }
 
         // tokens on each query's whole path (parents come before children in preorder)
         {
@@ -156,11 +187,73 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
         const int32_t S = chunk_size;
         int64_t flat = 0;
         bool open = false;
+        int32_t at_i = 0, at_done = 0;  // where the split loops are: position in `pre`, tokens of that node already placed
+
+        // ---- chunks taken over from prev: all that end in front of the first node whose tokens differ ----
+        int32_t i_resume = 0, done_resume = 0, c_keep = 0;
+        if (same_topology && prev->chunk_size == chunk_size && prev->flags == flags && mode != DEFT_GROUP_QUERY) {
+            auto differs = [&](int32_t u) {
+                if (prev->in_tok_len[u] != node_tok_len[u]) return true;
+                const int32_t a0 = prev->in_ext_ptr[u], a1 = prev->in_ext_ptr[u + 1], b0 = ext.ptr[u], b1 = ext.ptr[u + 1];
+                if (a1 - a0 != b1 - b0) return true;
+                for (int32_t k = 0; k < a1 - a0; ++k)
+                    if (prev->in_ext_begin[a0 + k] != ext.begin[b0 + k] || prev->in_ext_len[a0 + k] != ext.len[b0 + k])
+                        return true;
+                return false;
+            };
+            int32_t i0 = 0;
+            while (i0 < n && !differs(pre[i0])) ++i0;
+            // A chunk is taken over if the chunk behind it also starts in front of the first change: what closed it
+            // (it was full, or the next piece would have made it too dear) is then the same as before.  The split
+            // goes on where the first chunk not taken over started.
+            const int32_t m_prev = prev->n_chunks();
+            while (c_keep + 1 < m_prev && prev->chunk_first_i[c_keep + 1] < i0) ++c_keep;
+            if (m_prev > 0) {
+                i_resume = prev->chunk_first_i[c_keep];
+                done_resume = prev->chunk_first_done[c_keep];
+                flat = prev->chunk_flat_begin[c_keep];
+            }
+            const int32_t s_keep = m_prev > 0 ? prev->chunk_seg_ptr[c_keep] : 0;
+            auto head = [](std::vector<int32_t> &dst, const std::vector<int32_t> &src, int32_t cnt) {
+                dst.assign(src.begin(), src.begin() + cnt);
+            };
+            head(P->chunk_seg_ptr, prev->chunk_seg_ptr, c_keep);
+            head(P->chunk_first_i, prev->chunk_first_i, c_keep);
+            head(P->chunk_first_done, prev->chunk_first_done, c_keep);
+            head(P->chunk_last_i, prev->chunk_last_i, c_keep);
+            P->chunk_flat_begin.assign(prev->chunk_flat_begin.begin(), prev->chunk_flat_begin.begin() + c_keep);
+            head(P->seg_tok_begin, prev->seg_tok_begin, s_keep);
+            head(P->seg_len, prev->seg_len, s_keep);
+            head(P->seg_qlo, prev->seg_qlo, s_keep);
+            head(P->seg_qhi, prev->seg_qhi, s_keep);
+            head(P->seg_node, prev->seg_node, s_keep);
+            head(P->chunk_qlo, prev->chunk_qlo, c_keep);
+            head(P->chunk_qhi, prev->chunk_qhi, c_keep);
+            if (m_prev > 0) {
+                head(P->chunk_slot_base, prev->chunk_slot_base, c_keep + 1);
+                head(P->seg_mask_ptr, prev->seg_mask_ptr, s_keep + 1);
+                P->seg_mask.assign(prev->seg_mask.begin(), prev->seg_mask.begin() + prev->seg_mask_ptr[s_keep]);
+            }
+        }
+
+        {
+            // room for the usual number of pieces: one per extent plus one per cut
+            const size_t guess = ext.len.size() + (size_t)(ntok / S) + 8;
+            for (std::vector<int32_t> *v : {&P->seg_tok_begin, &P->seg_len, &P->seg_qlo, &P->seg_qhi, &P->seg_node,
+                                            &P->seg_mask_ptr})
+                v->reserve(guess);
+            P->seg_mask.reserve(guess);
+        }
         auto piece = [&](int32_t begin, int32_t len, int32_t lo, int32_t hi, int32_t node) {
             if (!open) {
                 P->chunk_seg_ptr.push_back(P->n_segs());
+                P->chunk_first_i.push_back(at_i);
+                P->chunk_first_done.push_back(at_done);
+                P->chunk_last_i.push_back(at_i);
+                P->chunk_flat_begin.push_back(flat);
                 open = true;
             }
+            P->chunk_last_i.back() = at_i;
             P->seg_tok_begin.push_back(begin);
             P->seg_len.push_back(len);
             P->seg_qlo.push_back(lo);
@@ -188,10 +281,10 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
             case DEFT_SPLIT_FLATTEN: {
                 // Flattened Tree KV Splitting (Remark 3.1): depth-first order, a cut every S tokens
                 int32_t room = S;
-                for (int32_t i = 0; i < n; ++i) {
+                for (int32_t i = i_resume; i < n; ++i) {
                     const int32_t u = pre[i];
                     if (!reached(u)) continue;
-                    int32_t done = 0;
+                    int32_t done = i == i_resume ? done_resume : 0;
                     const int32_t len = node_tok_len[u];
                     while (done < len) {
                         if (room == 0) {
@@ -199,6 +292,8 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
                             room = S;
                         }
                         const int32_t take = std::min(room, len - done);
+                        at_i = i;
+                        at_done = done;
                         node_range(u, done, take, P->node_q_lo[u], P->node_q_hi[u]);
                         done += take;
                         room -= take;
@@ -208,19 +303,23 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
             }
             case DEFT_SPLIT_NODE:
                 // DeFT-Node (Algorithm 1): one group per tree node, whatever its length
-                for (int32_t i = 0; i < n; ++i) {
+                for (int32_t i = i_resume; i < n; ++i) {
                     const int32_t u = pre[i];
                     if (!reached(u)) continue;
+                    at_i = i;
+                    at_done = 0;
                     node_range(u, 0, node_tok_len[u], P->node_q_lo[u], P->node_q_hi[u]);
                     close();
                 }
                 break;
             case DEFT_SPLIT_NODE_CHUNK:
                 // DeFT-Node-Chunk: node-wise groups, every node cut into blocks of S tokens on its own
-                for (int32_t i = 0; i < n; ++i) {
+                for (int32_t i = i_resume; i < n; ++i) {
                     const int32_t u = pre[i];
                     if (!reached(u)) continue;
-                    for (int32_t done = 0; done < node_tok_len[u]; done += S) {
+                    for (int32_t done = i == i_resume ? done_resume : 0; done < node_tok_len[u]; done += S) {
+                        at_i = i;
+                        at_done = done;
                         node_range(u, done, std::min(S, node_tok_len[u] - done), P->node_q_lo[u], P->node_q_hi[u]);
                         close();
                     }
@@ -242,6 +341,8 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
                                 room = S;
                             }
                             const int32_t take = std::min(room, len - done);
+                            at_i = 0;  // chunks of this split are never taken over by a later plan
+                            at_done = 0;
                             node_range(u, done, take, pos, pos + 1);
                             done += take;
                             room -= take;
@@ -271,12 +372,12 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
                 };
                 int64_t held = 0;
                 int32_t c_lo = 0, c_hi = 0;
-                for (int32_t i = 0; i < n; ++i) {
+                for (int32_t i = i_resume; i < n; ++i) {
                     const int32_t u = pre[i];
                     if (!reached(u)) continue;
                     const int32_t u_lo = P->node_q_lo[u], u_hi = P->node_q_hi[u];
                     const Weight own = weight(u_hi - u_lo);
-                    int32_t done = 0;
+                    int32_t done = i == i_resume ? done_resume : 0;
                     const int32_t len = node_tok_len[u];
                     while (done < len) {
                         const int64_t left = len - done;
@@ -296,6 +397,8 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
                         } else {
                             take = std::min<int64_t>(left, limit(own.tasks));
                         }
+                        at_i = i;
+                        at_done = done;
                         node_range(u, done, (int32_t)take, u_lo, u_hi);
                         held += take;
                         c_lo = lo;
@@ -323,11 +426,14 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
         }
 
         // ---- KV-guided grouping: the queries of each chunk, and the slots of their partials ----
+        // (chunks taken over from an earlier plan bring their groups, slots and masks with them)
+        if (c_keep > m) return DEFT_EINVAL;  // cannot happen: the split only appends
         P->chunk_qlo.resize(m);
         P->chunk_qhi.resize(m);
-        P->chunk_slot_base.assign(m + 1, 0);
-        int64_t slots = 0;
-        for (int32_t c = 0; c < m; ++c) {
+        if (P->chunk_slot_base.empty()) P->chunk_slot_base.assign(1, 0);
+        int64_t slots = P->chunk_slot_base[c_keep];
+        P->chunk_slot_base.resize(m + 1);
+        for (int32_t c = c_keep; c < m; ++c) {
             int32_t lo = INT32_MAX, hi = INT32_MIN;
             for (int32_t s = P->chunk_seg_ptr[c]; s < P->chunk_seg_ptr[c + 1]; ++s) {
                 lo = std::min(lo, P->seg_qlo[s]);
@@ -341,8 +447,8 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
         }
 
         // ---- bit causal masks --------------------------------------------------------------------
-        P->seg_mask_ptr.assign(1, 0);
-        for (int32_t c = 0; c < m; ++c) {
+        if (P->seg_mask_ptr.empty()) P->seg_mask_ptr.assign(1, 0);
+        for (int32_t c = c_keep; c < m; ++c) {
             const int32_t lo = P->chunk_qlo[c], w = P->chunk_qhi[c] - lo;
             const int32_t words = (w + 63) / 64;
             for (int32_t s = P->chunk_seg_ptr[c]; s < P->chunk_seg_ptr[c + 1]; ++s) {
@@ -386,13 +492,18 @@ int plan_impl(const NodeExtents &ext, const int32_t *node_tok_len, const int32_t
 
 }  // namespace
 
-extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_len, const int32_t *node_parent,
-                         int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size,
-                         uint32_t flags, deft_plan_t **out_plan) {
+namespace {
+
+int plan_contiguous(const int32_t *node_tok_begin, const int32_t *node_tok_len, const int32_t *node_parent,
+                    int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size,
+                    uint32_t flags, deft_plan_t **out_plan, const deft_plan_t *prev) {
     if (out_plan) *out_plan = nullptr;
     if (!out_plan || !node_tok_begin || !node_tok_len || !node_parent || n_nodes < 1) return DEFT_EINVAL;
     try {
         NodeExtents ext;
+        ext.ptr.reserve((size_t)n_nodes + 1);
+        ext.begin.reserve((size_t)n_nodes);
+        ext.len.reserve((size_t)n_nodes);
         ext.ptr.assign(1, 0);
         for (int32_t u = 0; u < n_nodes; ++u) {
             if (node_tok_begin[u] < 0 || node_tok_len[u] < 0 || (int64_t)node_tok_begin[u] + node_tok_len[u] > ntok)
@@ -403,16 +514,15 @@ extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_
             }
             ext.ptr.push_back((int32_t)ext.len.size());
         }
-        return plan_impl(ext, node_tok_len, node_parent, n_nodes, query_node, nq, ntok, chunk_size, flags, out_plan);
+        return plan_impl(ext, node_tok_len, node_parent, n_nodes, query_node, nq, ntok, chunk_size, flags, out_plan, prev);
     } catch (const std::bad_alloc &) {
         return DEFT_ENOMEM;
     }
 }
 
-extern "C" int deft_plan_paged(const int32_t *node_page_ptr, const int32_t *page_ids, int32_t page_size,
-                               int32_t n_pool_pages, const int32_t *node_tok_len, const int32_t *node_parent,
-                               int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t chunk_size,
-                               uint32_t flags, deft_plan_t **out_plan) {
+int plan_paged(const int32_t *node_page_ptr, const int32_t *page_ids, int32_t page_size, int32_t n_pool_pages,
+               const int32_t *node_tok_len, const int32_t *node_parent, int32_t n_nodes, const int32_t *query_node,
+               int32_t nq, int32_t chunk_size, uint32_t flags, deft_plan_t **out_plan, const deft_plan_t *prev) {
     if (out_plan) *out_plan = nullptr;
     if (!out_plan || !node_page_ptr || !node_tok_len || !node_parent || n_nodes < 1) return DEFT_EINVAL;
     if (page_size < 1 || n_pool_pages < 0 || (int64_t)page_size * n_pool_pages > INT32_MAX) return DEFT_EINVAL;
@@ -440,10 +550,42 @@ extern "C" int deft_plan_paged(const int32_t *node_page_ptr, const int32_t *page
             ext.ptr.push_back((int32_t)ext.len.size());
         }
         return plan_impl(ext, node_tok_len, node_parent, n_nodes, query_node, nq, n_pool_pages * page_size,
-                         chunk_size, flags, out_plan);
+                         chunk_size, flags, out_plan, prev);
     } catch (const std::bad_alloc &) {
         return DEFT_ENOMEM;
     }
+}
+
+}  // namespace
+
+extern "C" int deft_plan(const int32_t *node_tok_begin, const int32_t *node_tok_len, const int32_t *node_parent,
+                         int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t ntok, int32_t chunk_size,
+                         uint32_t flags, deft_plan_t **out_plan) {
+    return plan_contiguous(node_tok_begin, node_tok_len, node_parent, n_nodes, query_node, nq, ntok, chunk_size, flags,
+                           out_plan, nullptr);
+}
+
+extern "C" int deft_plan_paged(const int32_t *node_page_ptr, const int32_t *page_ids, int32_t page_size,
+                               int32_t n_pool_pages, const int32_t *node_tok_len, const int32_t *node_parent,
+                               int32_t n_nodes, const int32_t *query_node, int32_t nq, int32_t chunk_size,
+                               uint32_t flags, deft_plan_t **out_plan) {
+    return plan_paged(node_page_ptr, page_ids, page_size, n_pool_pages, node_tok_len, node_parent, n_nodes, query_node,
+                      nq, chunk_size, flags, out_plan, nullptr);
+}
+
+extern "C" int deft_plan_update(const deft_plan_t *prev, const int32_t *node_tok_begin, const int32_t *node_tok_len,
+                                const int32_t *node_parent, int32_t n_nodes, const int32_t *query_node, int32_t nq,
+                                int32_t ntok, int32_t chunk_size, uint32_t flags, deft_plan_t **out_plan) {
+    return plan_contiguous(node_tok_begin, node_tok_len, node_parent, n_nodes, query_node, nq, ntok, chunk_size, flags,
+                           out_plan, prev);
+}
+
+extern "C" int deft_plan_paged_update(const deft_plan_t *prev, const int32_t *node_page_ptr, const int32_t *page_ids,
+                                      int32_t page_size, int32_t n_pool_pages, const int32_t *node_tok_len,
+                                      const int32_t *node_parent, int32_t n_nodes, const int32_t *query_node, int32_t nq,
+                                      int32_t chunk_size, uint32_t flags, deft_plan_t **out_plan) {
+    return plan_paged(node_page_ptr, page_ids, page_size, n_pool_pages, node_tok_len, node_parent, n_nodes, query_node,
+                      nq, chunk_size, flags, out_plan, prev);
 }
 
 // Chunk size that fills an MI355X once.  Stage 1 runs one workgroup per (chunk, KV head, 128 rows of the

@@ -66,6 +66,32 @@ int main() {
             if (deft_workspace_bytes(plan, 8, 2, 128) == 0) return 4;
             chunks += v.n_chunks;
             ++plans;
+            // the tree after a decode iteration or two, planned from the old plan and from scratch: same sizes
+            for (int round = 0; round < 2; ++round) {
+                for (int32_t u = 0; u < n; ++u)
+                    if (len[u] > 0 && below(3) == 0 && u + 1 < n && begin[u] + len[u] < begin[u + 1]) ++len[u];
+                if (below(5) == 0 && nq) qn[below(nq)] = below(n);
+                deft_plan_t *next = nullptr, *fresh = nullptr;
+                const int r1 = deft_plan_update(plan, begin.data(), len.data(), parent.data(), n, nq ? qn.data() : nullptr, nq,
+                                                ntok, chunk, flags, &next);
+                const int r2 = deft_plan(begin.data(), len.data(), parent.data(), n, nq ? qn.data() : nullptr, nq, ntok, chunk,
+                                         flags, &fresh);
+                if (r1 != r2) return 7;
+                if (r1 == DEFT_OK) {
+                    deft_plan_view_t a, b;
+                    deft_plan_view(next, &a);
+                    deft_plan_view(fresh, &b);
+                    if (a.n_chunks != b.n_chunks || a.n_segs != b.n_segs || a.n_slots != b.n_slots || a.n_flat != b.n_flat) return 8;
+                    for (int32_t i = 0; i < a.n_segs; ++i)
+                        if (a.seg_tok_begin[i] != b.seg_tok_begin[i] || a.seg_len[i] != b.seg_len[i]) return 9;
+                    deft_plan_destroy(plan);
+                    plan = next;
+                    deft_plan_destroy(fresh);
+                    ++plans;
+                } else {
+                    break;
+                }
+            }
             deft_plan_destroy(plan);
         } else {
             if (plan) return 5;
