@@ -61,6 +61,8 @@ def parse_args():
                          "binding.alloc_kv_cache, which staggers the V pool by half a KiB")
     ap.add_argument("--precise", action="store_true", help="DEFT_PRECISE_WEIGHTS: two-term softmax weights everywhere")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle (no cpu_baseline, no parity check)")
+    ap.add_argument("--no-equal-token", action="store_true",
+                    help="do not also measure the paper's equal-token split (profiling runs: one split per run)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a few plain 1 GiB device-to-device copies (known size) so that a rocprofv3 "
                          "--pmc run of this command can scale its FETCH_SIZE / WRITE_SIZE readings")
@@ -386,7 +388,7 @@ def measure(cfg, args, lib, dev, with_oracle, cpu_seconds):
         rec["oracle_us"] = round(cpu_us, 1)
         detail["cpu"] = {"us": cpu_us, "cores": used, "reps": reps}
     # the paper's equal-token split (Remark 3.1) on the same buffers, next to the default split
-    if args.mode != "flatten" and args.chunk == 0 and w.P == 0:
+    if args.mode != "flatten" and args.chunk == 0 and w.P == 0 and not args.no_equal_token:
         w.release()
         w.set_split("flatten")
         w.set_chunk(0)
