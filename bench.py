@@ -164,6 +164,7 @@ class Workload:
         self.layer_ptrs = [(vp(self.qs[i].data_ptr()), vp(self.ks[i].data_ptr()), vp(self.vs[i].data_ptr()),
                             vp(self.outs[i].data_ptr())) for i in range(L)]
         self.plans = []
+        self.ready = None
         self.set_chunk(args.chunk)
 
     def set_split(self, mode):
@@ -222,6 +223,7 @@ class Workload:
             raise RuntimeError("plan image grew")
         self.check(lib.deft_plan_upload(h, Hq, Hkv, self.imgp, self.img_bytes, self.st), "deft_plan_upload")
         self.plans.append(h)
+        self.ready = h  # the plan whose image sits in imgp
         return h
 
     def step(self):
@@ -240,16 +242,20 @@ class Workload:
         import torch
 
         lib, Hq, Hkv, d, L = self.lib, self.Hq, self.Hkv, self.d, self.L
-        h = self.plans[-1] if self.plans else self.prepare()
+        h = self.ready if self.ready is not None else self.prepare()
         s1, s2 = [], []
         for _ in range(n_rep):
             e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
             e0.record(self.stream)
             for (qp, kp, vpp, op) in self.layer_ptrs:
-                lib.deft_stage1_partial_attention(h, self.imgp, qp, kp, vpp, Hq, Hkv, d, 0.0, self.wsp, self.ws_bytes, self.st)
+                rc = lib.deft_stage1_partial_attention(h, self.imgp, qp, kp, vpp, Hq, Hkv, d, 0.0, self.wsp, self.ws_bytes, self.st)
+                if rc != 0:
+                    self.check(rc, "deft_stage1_partial_attention")
             e1.record(self.stream)
             for (qp, kp, vpp, op) in self.layer_ptrs:
-                lib.deft_stage2_global_reduction(h, self.imgp, op, Hq, Hkv, d, 0.0, 0, self.wsp, self.ws_bytes, self.st)
+                rc = lib.deft_stage2_global_reduction(h, self.imgp, op, Hq, Hkv, d, 0.0, 0, self.wsp, self.ws_bytes, self.st)
+                if rc != 0:
+                    self.check(rc, "deft_stage2_global_reduction")
             e2.record(self.stream)
             torch.cuda.synchronize()
             s1.append(e0.elapsed_time(e1) / L * 1e3)
@@ -260,6 +266,7 @@ class Workload:
         for h in self.plans:
             self.lib.deft_plan_destroy(h)
         self.plans = []
+        self.ready = None
 
 
 def measure(cfg, args, lib, dev, with_oracle, cpu_seconds):
@@ -304,7 +311,7 @@ def measure(cfg, args, lib, dev, with_oracle, cpu_seconds):
         hs = [ctypes.c_void_p() for _ in range(10)]
         tu0 = time.perf_counter()
         for h_new in hs:
-            w.check(lib.deft_plan_update(w.plans[-1], w.nbp, w.nlp, w.parp, tree.n_nodes, w.qnp, tree.nq, tree.ntok,
+            w.check(lib.deft_plan_update(w.ready, w.nbp, w.nlp, w.parp, tree.n_nodes, w.qnp, tree.nq, tree.ntok,
                                          w.chunk, w.mode_flag, ctypes.byref(h_new)), "deft_plan_update")
         update_us = (time.perf_counter() - tu0) * 1e5
         w.plans.extend(hs)
@@ -313,14 +320,14 @@ def measure(cfg, args, lib, dev, with_oracle, cpu_seconds):
     s1_us, s2_us = float(np.mean(s1)), float(np.mean(s2))
 
     # the same call with one replica only (layer 0 every time): the memory-side cache then holds part of K/V
-    h = w.plans[-1]
+    h = w.ready
     ew0, ew1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     qp, kp, vpp, op = w.layer_ptrs[0]
     spare = torch.empty_like(w.outs[0])
     ew0.record(w.stream)
     for _ in range(L):
-        lib.deft_tree_attn_decode(h, w.imgp, qp, kp, vpp, ctypes.c_void_p(spare.data_ptr()), w.Hq, w.Hkv, w.d, 0.0, 0,
-                                  w.wsp, w.ws_bytes, w.st)
+        w.check(lib.deft_tree_attn_decode(h, w.imgp, qp, kp, vpp, ctypes.c_void_p(spare.data_ptr()), w.Hq, w.Hkv, w.d, 0.0, 0,
+                                          w.wsp, w.ws_bytes, w.st), "deft_tree_attn_decode")
     ew1.record(w.stream)
     torch.cuda.synchronize()
     warm_us = ew0.elapsed_time(ew1) / L * 1e3
