@@ -308,8 +308,9 @@ int deft_tree_attn_decode_static(const deft_plan_t *plan, const void *dev_image,
                                  uint32_t flags, void *stream);
 
 /*
- * Measurement aid: reads `bytes` bytes at dev_buf once with 128-bit loads from every compute unit
- * (DEFT_PROBE_SINK_BYTES / 4 workgroups, grid-stride) and stores, for each workgroup, the xor of the
+ * Benchmark aid, not part of the method (no decode call uses it; it exists so that the benchmark can state
+ * the machine's read rate next to stage 1's).  Reads `bytes` bytes at dev_buf once with 128-bit loads from
+ * every compute unit (DEFT_PROBE_SINK_BYTES / 4 workgroups, grid-stride) and stores, for each workgroup, the xor of the
  * 32-bit words it read into dev_sink (device, DEFT_PROBE_SINK_BYTES bytes, 4-byte aligned; all of it is
  * overwritten), so the xor over the sink is the xor over the buffer.  The rate it reaches is the
  * read-stream ceiling against which the benchmark states the KV read rate of stage 1 (the method is
