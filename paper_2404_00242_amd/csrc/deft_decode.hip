@@ -97,6 +97,8 @@ static_assert(4 * DEFT_MAX_CHUNK * sizeof(int32_t) <= kXbufBytes, "piece records
 // What a wave needs to know about its chunk to address tokens.
 struct ChunkCtx {
     const uint16_t *kbase, *vbase;  // K/V pointers already offset to this head and this lane's d slice
+    const uint16_t *khead, *vhead;  // the same without the lane's slice (wave-uniform), and the slices in bytes
+    uint32_t klane, vlane;
     size_t row_stride;              // elements between consecutive token rows
     const int32_t *s_row, *s_qlo, *s_qhi;  // LDS per-token table (only when !uniform), padded to whole blocks
     int clen;                       // tokens in the chunk
@@ -177,12 +179,15 @@ struct TileState {
 // handful of rounded weights does not average out and an output element would be off by up to
 // 2^-7 * sum_t w_t |V_t|.  The matrix pipe has the room (a bandwidth-bound block keeps it busy for a sixth
 // of its time).
-template <int D, int NT, bool PRECISE>
-__device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx &c, int x0, TileState<D> (&ts)[NT],
-                                              const float cs, const float lazy) {
+//
+// The pieces of a block's work, in the order compute_block strings them together.  The pipelined loop of the
+// wide tasks (WidePipe) calls them separately so that one block's weights and the next block's scores can be
+// issued side by side.
+
+// S^T = K Q^T : sacc[t][a][i] is the score of token 16a + 4g + i against row n16 of tile t
+template <int D, int NT>
+__device__ __forceinline__ void qk_block(const bf16x8 (&k)[2][D / 32], const TileState<D> (&ts)[NT], f32x4 (&sacc)[NT][2]) {
     constexpr int KK = D / 32;
-    // S^T = K Q^T : sacc[t][a][i] is the score of token 16a + 4g + i against row n16 of tile t
-    f32x4 sacc[NT][2];
 #pragma unroll
     for (int aa = 0; aa < 2; ++aa)
 #pragma unroll
@@ -190,13 +195,16 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.k[aa][kk], ts[t].q[kk], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[aa][kk], ts[t].q[kk], acc, 0, 0, 0);
             sacc[t][aa] = acc;
         }
+}
 
-    // mask: a token is visible to plan position qpos iff qlo <= qpos < qhi of the node piece it belongs to.
-    // A full block of a single-piece chunk is visible to every row of the chunk's group: nothing to mask
-    // (rows past the group's end have Q = 0, finite scores, and are never written).
+// mask: a token is visible to plan position qpos iff qlo <= qpos < qhi of the node piece it belongs to.
+// A full block of a single-piece chunk is visible to every row of the chunk's group: nothing to mask
+// (rows past the group's end have Q = 0, finite scores, and are never written).
+template <int D, int NT>
+__device__ __forceinline__ void mask_block(const ChunkCtx &c, int x0, const TileState<D> (&ts)[NT], f32x4 (&sacc)[NT][2]) {
     if (!(c.uniform && x0 + 32 <= c.clen)) {
 #pragma unroll
         for (int aa = 0; aa < 2; ++aa) {
@@ -222,17 +230,31 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
                 }
         }
     }
+}
 
-    bf16x8 preg[NT], plo[NT];
+// lazy reference: raise it (for every tile of the wave) only when some score exceeds it by more than `lazy`
+template <int D, int NT>
+__device__ __forceinline__ void raise_block(TileState<D> (&ts)[NT], const f32x4 (&sacc)[NT][2], const float cs,
+                                            const float lazy) {
+    // the common case only needs to know whether any score is above the threshold: eight compares per tile
+    // (their lane masks are combined on the scalar unit); the maximum itself is formed in the rare branch
+    bool need = false;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        RowState &st = ts[t].rs;
-        float mx = fmaxf(fmaxf(fmaxf(sacc[t][0][0], sacc[t][0][1]), fmaxf(sacc[t][0][2], sacc[t][0][3])),
-                         fmaxf(fmaxf(sacc[t][1][0], sacc[t][1][1]), fmaxf(sacc[t][1][2], sacc[t][1][3])));
-        if (__any(mx > st.m + lazy)) {
+        const float thr = ts[t].rs.m + lazy;
+#pragma unroll
+        for (int aa = 0; aa < 2; ++aa)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) need = need || (sacc[t][aa][i] > thr);
+    }
+    if (__any(need)) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
             // raise the reference of every row to its exact running maximum and rescale what was accumulated
-            mx = wave_row_max(mx);
-            const float m_new = fmaxf(st.m, mx);
+            RowState &st = ts[t].rs;
+            const float mx = fmaxf(fmaxf(fmaxf(sacc[t][0][0], sacc[t][0][1]), fmaxf(sacc[t][0][2], sacc[t][0][3])),
+                                   fmaxf(fmaxf(sacc[t][1][0], sacc[t][1][1]), fmaxf(sacc[t][1][2], sacc[t][1][3])));
+            const float m_new = fmaxf(st.m, wave_row_max(mx));
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
             const float alpha = __builtin_amdgcn_exp2f(st.m * cs - m_use * cs);  // exp2(-inf) = 0 on the first raise
             st.m = m_new;
@@ -241,16 +263,25 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
 #pragma unroll
             for (int cc = 0; cc < 8; ++cc) ts[t].o[cc] *= alpha;
         }
+    }
+}
+
+// weights of the block as bf16 B operands (PRECISE: plus what the rounding to bf16 dropped, itself rounded to
+// bf16; hi widens to fp32 by a 16-bit shift)
+template <int D, int NT, bool PRECISE>
+__device__ __forceinline__ void weights_block(const TileState<D> (&ts)[NT], const f32x4 (&sacc)[NT][2], const float cs,
+                                              bf16x8 (&preg)[NT], bf16x8 (&plo)[NT]) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
         float pv[8];
 #pragma unroll
         for (int aa = 0; aa < 2; ++aa)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pv[4 * aa + i] = __builtin_amdgcn_exp2f(fmaf(sacc[t][aa][i], cs, -st.mc));
+            for (int i = 0; i < 4; ++i) pv[4 * aa + i] = __builtin_amdgcn_exp2f(fmaf(sacc[t][aa][i], cs, -ts[t].rs.mc));
         const u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]),
                           pack_bf16(pv[6], pv[7])};
         preg[t] = __builtin_bit_cast(bf16x8, pk);
         if (PRECISE) {
-            // what the rounding to bf16 dropped, itself rounded to bf16 (hi widens to fp32 by a 16-bit shift)
             u32x4 lk;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -261,8 +292,12 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
             plo[t] = __builtin_bit_cast(bf16x8, lk);
         }
     }
+}
 
-    // l += column sums of P^T
+// l += column sums of P^T;  O^T += V^T P^T
+template <int D, int NT, bool PRECISE>
+__device__ __forceinline__ void pv_block(const u32x4 (&v)[8], const bf16x8 (&preg)[NT], const bf16x8 (&plo)[NT],
+                                         TileState<D> (&ts)[NT]) {
     {
         const u32x4 one4 = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // eight bf16 1.0
         const bf16x8 ones = __builtin_bit_cast(bf16x8, one4);
@@ -272,15 +307,14 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
             if (PRECISE) ts[t].rs.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, plo[t], ts[t].rs.l, 0, 0, 0);
         }
     }
-
-    // O^T += V^T P^T.  The V^T operand of product c' = 2*c2 + {0,1} is a 16-bit interleave of token pairs:
+    // The V^T operand of product c' = 2*c2 + {0,1} is a 16-bit interleave of token pairs:
     // vt[p] = {V[tok 2p][8*n16 + c'], V[tok 2p+1][8*n16 + c']}
 #pragma unroll
     for (int c2 = 0; c2 < 4; ++c2) {
         u32x4 vt_lo, vt_hi;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-            const uint32_t lo = r.v[2 * p][c2], hi = r.v[2 * p + 1][c2];
+            const uint32_t lo = v[2 * p][c2], hi = v[2 * p + 1][c2];
             vt_lo[p] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
             vt_hi[p] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
         }
@@ -298,6 +332,18 @@ __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx
             }
         }
     }
+}
+
+template <int D, int NT, bool PRECISE>
+__device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx &c, int x0, TileState<D> (&ts)[NT],
+                                              const float cs, const float lazy) {
+    f32x4 sacc[NT][2];
+    qk_block<D, NT>(r.k, ts, sacc);
+    mask_block<D, NT>(c, x0, ts, sacc);
+    raise_block<D, NT>(ts, sacc, cs, lazy);
+    bf16x8 preg[NT], plo[NT];
+    weights_block<D, NT, PRECISE>(ts, sacc, cs, preg, plo);
+    pv_block<D, NT, PRECISE>(r.v, preg, plo, ts);
 }
 
 // ---- token-split path (groups of one row tile): every wave streams its own blocks, two in flight ----
@@ -430,6 +476,139 @@ struct SharedPipe {
     }
 };
 
+// ---- row-split path for groups of 3 to 8 row tiles (TR = 4: the four waves share every block), pipelined
+//      across blocks.  A wave's vector work on a block (32 exponentials and their scaling and packing, for two
+//      tiles) takes longer than the block's MFMAs, and inside one basic block the matrix pipe and the vector
+//      pipe run side by side; so the weights of block b-1 are formed while the scores of block b are
+//      multiplied, and the P.V products of block b-1 follow.  Between two barriers a wave therefore holds the
+//      scores and V of one block and K of the next.
+//      UNIFORM: the chunk is one piece of one node, so its rows are consecutive.  A whole block's share is
+//      then addressed as (wave-uniform pointer that moves on by one block per step) + (a byte offset per lane
+//      that never changes): no vector arithmetic per load.  The last, partial block and the dummy loads past
+//      the end go through the general addressing.
+template <int D, int NT, bool UNIFORM>
+struct WidePipe {
+    static constexpr int KK = D / 32;
+    using S = Share<D, 4>;
+    static constexpr int DEPTH = NT == 1 ? 1 : 2;  // blocks whose shares a wave keeps in flight (see SharedPipe)
+    S st[DEPTH];
+    uint32_t lane_row, lane_col;  // UNIFORM: first row of this lane's loads inside a block, byte offset inside a row
+
+    // UNIFORM: load q of the share is (wave-uniform pointer of the block) + (row of the lane, clamped to the
+    // chunk's last row) * row bytes + the lane's column; a K loader reads four 64-byte columns of one row, a V
+    // loader one column of four rows.  No branch on any path: blocks past the end repeat the last block, so the same four load instructions are
+    // issued whatever happens and the compiler's s_waitcnt vmcnt counts stay exact.
+    __device__ __forceinline__ void issue(S &sh, const ChunkCtx &c, int t, int blk, int nblk) {
+        if (UNIFORM) {
+            static_assert(KK == 4 || !UNIFORM, "a K loader issues four loads");
+            const int blk_e = min(blk, nblk - 1);
+            const uint32_t row_bytes = (uint32_t)c.row_stride * 2;
+            const size_t first = ((size_t)c.begin0 + 32 * (size_t)blk_e) * row_bytes;
+            const int lim = min(31, c.clen - 1 - 32 * blk_e);  // last row of the block that exists
+            const bool kl = t < 2;
+            const char *base = reinterpret_cast<const char *>(kl ? c.khead : c.vhead) + first;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                // K loader: four 64-byte columns of row lane_row; V loader: rows lane_row .. lane_row + 3
+                const int row = min((int)lane_row + (kl ? 0 : q), lim);
+                const uint32_t off = (uint32_t)row * row_bytes + lane_col + (kl ? 64u * q : 0u);
+                sh.x[q] = *reinterpret_cast<const u32x4 *>(base + off);
+            }
+        } else {
+            share_issue<D, 4>(sh, c, t, blk * 32, blk < nblk);
+        }
+    }
+
+    __device__ __forceinline__ void prime(const ChunkCtx &ctx, int wave, int nblk) {
+        lane_row = wave < 2 ? 16 * wave + ctx.n16 : 16 * (wave - 2) + 4 * ctx.g;
+        lane_col = wave < 2 ? ctx.klane : ctx.vlane;
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) issue(st[u], ctx, wave, u, nblk);
+    }
+
+    // pass this wave's share of a block to the others and fetch the share of a later block
+    __device__ __forceinline__ void exchange(S &sh, const ChunkCtx &c, u32x4 *xs, int t, int lane, int next_blk, int nblk) {
+        if (t < 2) {
+#pragma unroll
+            for (int q = 0; q < KK; ++q) xs[(t * KK + q) * 64 + lane] = sh.x[q];
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) xs[(2 * KK + 4 * (t - 2) + q) * 64 + lane] = sh.x[q];
+        }
+        __syncthreads();
+        issue(sh, c, t, next_blk, nblk);
+    }
+    static __device__ __forceinline__ void read_k(const u32x4 *xs, int lane, bf16x8 (&k)[2][KK]) {
+#pragma unroll
+        for (int aa = 0; aa < 2; ++aa)
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) k[aa][kk] = __builtin_bit_cast(bf16x8, xs[(aa * KK + kk) * 64 + lane]);
+    }
+    static __device__ __forceinline__ void read_v(const u32x4 *xs, int lane, u32x4 (&v)[8]) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = xs[(2 * KK + j) * 64 + lane];
+    }
+
+    // one steady-state step: block `blk` arrives, block blk-1 (scores in sacc, V in vreg) is finished
+    template <bool PRECISE>
+    __device__ __forceinline__ void step(S &sh, const ChunkCtx &c, u32x4 *xs, int t, int lane, int blk, int nblk,
+                                         TileState<D> (&ts)[NT], f32x4 (&sacc)[NT][2], u32x4 (&vreg)[8], float cs,
+                                         float lazy) {
+        exchange(sh, c, xs, t, lane, blk + DEPTH, nblk);
+        bf16x8 k[2][KK];
+        read_k(xs, lane, k);
+        bf16x8 preg[NT], plo[NT];
+        f32x4 snew[NT][2];
+        weights_block<D, NT, PRECISE>(ts, sacc, cs, preg, plo);
+        qk_block<D, NT>(k, ts, snew);
+        pv_block<D, NT, PRECISE>(vreg, preg, plo, ts);
+        read_v(xs, lane, vreg);
+        mask_block<D, NT>(c, blk * 32, ts, snew);
+        raise_block<D, NT>(ts, snew, cs, lazy);
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) {
+            sacc[tt][0] = snew[tt][0];
+            sacc[tt][1] = snew[tt][1];
+        }
+    }
+
+    template <bool PRECISE>
+    __device__ __forceinline__ void run(const ChunkCtx &ctx, u32x4 *xbuf, int wave, int lane, int nblk,
+                                        TileState<D> (&ts)[NT], float cs, float lazy) {
+        const int t = wave;
+        constexpr int STAGE = S::NSLOT * 64;  // u32x4 per LDS exchange stage; stage (blk & 1) holds block blk
+        f32x4 sacc[NT][2];
+        u32x4 vreg[8];
+        {   // block 0: scores only
+            exchange(st[0], ctx, xbuf, t, lane, DEPTH, nblk);
+            bf16x8 k[2][KK];
+            read_k(xbuf, lane, k);
+            qk_block<D, NT>(k, ts, sacc);
+            read_v(xbuf, lane, vreg);
+            mask_block<D, NT>(ctx, 0, ts, sacc);
+            raise_block<D, NT>(ts, sacc, cs, lazy);
+        }
+        // steady state, DEPTH steps per round so that the shares in flight are addressed statically.  Whole
+        // rounds only inside the loop (a round that could stop half way would make the compiler assume, for the
+        // waits of the next round, that the share it consumes is the youngest one in flight).
+        int b0 = 1;
+        for (; b0 + DEPTH <= nblk; b0 += DEPTH) {
+#pragma unroll
+            for (int u = 0; u < DEPTH; ++u) {
+                const int blk = b0 + u;
+                step<PRECISE>(st[(1 + u) % DEPTH], ctx, xbuf + (blk & 1) * STAGE, t, lane, blk, nblk, ts, sacc, vreg, cs, lazy);
+            }
+        }
+        if (DEPTH == 2 && b0 < nblk)
+            step<PRECISE>(st[1], ctx, xbuf + (b0 & 1) * STAGE, t, lane, b0, nblk, ts, sacc, vreg, cs, lazy);
+        {   // last block: weights and products
+            bf16x8 preg[NT], plo[NT];
+            weights_block<D, NT, PRECISE>(ts, sacc, cs, preg, plo);
+            pv_block<D, NT, PRECISE>(vreg, preg, plo, ts);
+        }
+    }
+};
+
 // Stage 1: one workgroup of four waves per task = (chunk, KV head, up to 128 rows of the chunk's group).
 // The rows are (query of the group) x (query head reading this KV head), tiled 16 at a time.  A task of
 // 1, 2 or 3-4 tiles splits its rows over TR = 1, 2 or 4 waves and its tokens over the 4 / TR parts that
@@ -483,6 +662,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
     ctx.row_stride = (size_t)a.Hkv * D;
     ctx.kbase = a.k + (size_t)h * D + 8 * g;
     ctx.vbase = a.v + (size_t)h * D + 8 * (D == 128 ? n16 : (n16 & 7));
+    ctx.khead = a.k + (size_t)h * D;
+    ctx.vhead = a.v + (size_t)h * D;
+    ctx.klane = 16u * g;
+    ctx.vlane = 16u * (D == 128 ? n16 : (n16 & 7));
     ctx.s_row = s_row;
     ctx.s_qlo = s_qlo;
     ctx.s_qhi = s_qhi;
@@ -582,8 +765,13 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
         pipe.prime(ctx, wave, nblk);
         load_q(1);
         pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts1, a.c, lazy);
+    } else if (ctx.uniform) {
+        WidePipe<D, 2, D == 128> pipe;  // the fast addressing is written for four loads per K loader
+        pipe.prime(ctx, wave, nblk);
+        load_q(2);
+        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts, a.c, lazy);
     } else {
-        SharedPipe<D, 4, 2> pipe;
+        WidePipe<D, 2, false> pipe;
         pipe.prime(ctx, wave, nblk);
         load_q(2);
         pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts, a.c, lazy);
