@@ -143,19 +143,23 @@ __device__ __forceinline__ void load_block(KVRegs<D> &r, const ChunkCtx &c, int 
 }
 
 // Running softmax state of one row (held redundantly by the row's four lanes).
-//   m  : reference maximum of the raw scores, -inf while the row has seen no visible token
-//   mc : (m, or 0 while m is -inf) * cs, the value subtracted inside the exponential
-//   l  : sum over all tokens so far of the bf16-rounded exp2(s * cs - mc), i.e. of exactly the weights
-//        that enter the P.V product.  It is accumulated by one more MFMA per block whose A operand is all
-//        ones (every row of that product is the column sum of P^T), which costs the idle matrix pipe 16
-//        cycles instead of 8 VALU adds and leaves the total in every lane of the row.
+//   mc  : the reference subtracted inside the exponential, in units of the exponent: the weights are
+//         2^(s * cs - mc).  The row's reference maximum in units of the scores is mc / cs.
+//   thr : what an exponent s * cs - mc must exceed for the reference to be raised: kLazyLog2, or -inf while
+//         the row has seen no visible token (mc is 0 then and stands for "no reference yet")
+//   l   : sum over all tokens so far of the bf16-rounded weights, i.e. of exactly the numbers that enter the
+//         P.V product.  It is accumulated by one more MFMA per block whose A operand is all ones (every row
+//         of that product is the column sum of P^T), which costs the idle matrix pipe 16 cycles instead of 8
+//         VALU adds and leaves the total in every lane of the row.
 // The reference is only raised when some score exceeds it by more than kLazyLog2 / cs (probabilities may
 // then reach 2^kLazyLog2, harmless in bf16 and fp32); otherwise a block costs no cross-lane traffic and
 // no rescaling of the accumulators.  Any reference gives the same (m, l, acc) up to rounding, because the
 // merge of eq. 1 only needs the three to be consistent.
 struct RowState {
-    float m, mc;
+    float mc, thr;
     f32x4 l;  // four identical copies (rows 4g..4g+3 of the all-ones product)
+    // reference maximum in units of the scores, as the partial result states it
+    __device__ __forceinline__ float m(float inv_cs) const { return thr == -INFINITY ? -INFINITY : mc * inv_cs; }
 };
 constexpr float kLazyLog2 = 8.0f;
 
@@ -232,41 +236,54 @@ __device__ __forceinline__ void mask_block(const ChunkCtx &c, int x0, const Tile
     }
 }
 
-// lazy reference: raise it (for every tile of the wave) only when some score exceeds it by more than `lazy`
+// scores -> exponents of the weights: e = s * cs - mc, in place
 template <int D, int NT>
-__device__ __forceinline__ void raise_block(TileState<D> (&ts)[NT], const f32x4 (&sacc)[NT][2], const float cs,
-                                            const float lazy) {
-    // the common case only needs to know whether any score is above the threshold: eight compares per tile
-    // (their lane masks are combined on the scalar unit); the maximum itself is formed in the rare branch
-    bool need = false;
+__device__ __forceinline__ void shift_block(const TileState<D> (&ts)[NT], f32x4 (&sacc)[NT][2], const float cs) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const float thr = ts[t].rs.m + lazy;
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int aa = 0; aa < 2; ++aa)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) need = need || (sacc[t][aa][i] > thr);
+            for (int i = 0; i < 4; ++i) sacc[t][aa][i] = fmaf(sacc[t][aa][i], cs, -ts[t].rs.mc);
+}
+
+// lazy reference, on the shifted scores of shift_block: it is raised (for every tile of the wave) only when
+// some exponent exceeds kLazyLog2, i.e. some score exceeds the reference by more than kLazyLog2 / cs.  The
+// exponents come out of an fma, so their maximum needs no canonicalisation and takes four instructions per tile.
+template <int D, int NT>
+__device__ __forceinline__ void raise_block(TileState<D> (&ts)[NT], f32x4 (&sacc)[NT][2]) {
+    float mx[NT];
+    bool need = false;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        mx[t] = fmaxf(fmaxf(fmaxf(sacc[t][0][0], sacc[t][0][1]), fmaxf(sacc[t][0][2], sacc[t][0][3])),
+                      fmaxf(fmaxf(sacc[t][1][0], sacc[t][1][1]), fmaxf(sacc[t][1][2], sacc[t][1][3])));
+        need = need || (mx[t] > ts[t].rs.thr);
     }
     if (__any(need)) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            // raise the reference of every row to its exact running maximum and rescale what was accumulated
+            // move the reference of every row up to its running maximum (never down), rescale what was
+            // accumulated and move this block's exponents to the new reference
             RowState &st = ts[t].rs;
-            const float mx = fmaxf(fmaxf(fmaxf(sacc[t][0][0], sacc[t][0][1]), fmaxf(sacc[t][0][2], sacc[t][0][3])),
-                                   fmaxf(fmaxf(sacc[t][1][0], sacc[t][1][1]), fmaxf(sacc[t][1][2], sacc[t][1][3])));
-            const float m_new = fmaxf(st.m, wave_row_max(mx));
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(st.m * cs - m_use * cs);  // exp2(-inf) = 0 on the first raise
-            st.m = m_new;
-            st.mc = m_use * cs;
+            const float r = wave_row_max(mx[t]);  // largest exponent of the row in this block, -inf if all masked
+            const bool had = st.thr != -INFINITY;
+            const float d = had ? fmaxf(r, 0.f) : (r == -INFINITY ? 0.f : r);
+            const float alpha = had ? __builtin_amdgcn_exp2f(-d) : 0.f;  // nothing was accumulated before the first
+            st.mc += d;
+            st.thr = (had || r != -INFINITY) ? kLazyLog2 : -INFINITY;
             st.l *= alpha;
 #pragma unroll
             for (int cc = 0; cc < 8; ++cc) ts[t].o[cc] *= alpha;
+#pragma unroll
+            for (int aa = 0; aa < 2; ++aa)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sacc[t][aa][i] -= d;
         }
     }
 }
 
-// weights of the block as bf16 B operands (PRECISE: plus what the rounding to bf16 dropped, itself rounded to
+// weights of the block, 2^(shifted score), as bf16 B operands (PRECISE: plus what the rounding to bf16 dropped, itself rounded to
 // bf16; hi widens to fp32 by a 16-bit shift)
 template <int D, int NT, bool PRECISE>
 __device__ __forceinline__ void weights_block(const TileState<D> (&ts)[NT], const f32x4 (&sacc)[NT][2], const float cs,
@@ -277,7 +294,7 @@ __device__ __forceinline__ void weights_block(const TileState<D> (&ts)[NT], cons
 #pragma unroll
         for (int aa = 0; aa < 2; ++aa)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pv[4 * aa + i] = __builtin_amdgcn_exp2f(fmaf(sacc[t][aa][i], cs, -ts[t].rs.mc));
+            for (int i = 0; i < 4; ++i) pv[4 * aa + i] = __builtin_amdgcn_exp2f(sacc[t][aa][i]);
         const u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]),
                           pack_bf16(pv[6], pv[7])};
         preg[t] = __builtin_bit_cast(bf16x8, pk);
@@ -295,7 +312,9 @@ __device__ __forceinline__ void weights_block(const TileState<D> (&ts)[NT], cons
 }
 
 // l += column sums of P^T;  O^T += V^T P^T
-template <int D, int NT, bool PRECISE>
+// READY: v[2*c2] and v[2*c2 + 1] already are the interleaved operands vt_lo and vt_hi described below (the
+// waves that fetched V interleaved it before passing it on).
+template <int D, int NT, bool PRECISE, bool READY = false>
 __device__ __forceinline__ void pv_block(const u32x4 (&v)[8], const bf16x8 (&preg)[NT], const bf16x8 (&plo)[NT],
                                          TileState<D> (&ts)[NT]) {
     {
@@ -312,11 +331,16 @@ __device__ __forceinline__ void pv_block(const u32x4 (&v)[8], const bf16x8 (&pre
 #pragma unroll
     for (int c2 = 0; c2 < 4; ++c2) {
         u32x4 vt_lo, vt_hi;
+        if (READY) {
+            vt_lo = v[2 * c2];
+            vt_hi = v[2 * c2 + 1];
+        } else {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const uint32_t lo = v[2 * p][c2], hi = v[2 * p + 1][c2];
-            vt_lo[p] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-            vt_hi[p] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t lo = v[2 * p][c2], hi = v[2 * p + 1][c2];
+                vt_lo[p] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                vt_hi[p] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+            }
         }
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
@@ -336,11 +360,12 @@ __device__ __forceinline__ void pv_block(const u32x4 (&v)[8], const bf16x8 (&pre
 
 template <int D, int NT, bool PRECISE>
 __device__ __forceinline__ void compute_block(const KVRegs<D> &r, const ChunkCtx &c, int x0, TileState<D> (&ts)[NT],
-                                              const float cs, const float lazy) {
+                                              const float cs, const float inv_cs) {
     f32x4 sacc[NT][2];
     qk_block<D, NT>(r.k, ts, sacc);
     mask_block<D, NT>(c, x0, ts, sacc);
-    raise_block<D, NT>(ts, sacc, cs, lazy);
+    shift_block<D, NT>(ts, sacc, cs);
+    raise_block<D, NT>(ts, sacc);
     bf16x8 preg[NT], plo[NT];
     weights_block<D, NT, PRECISE>(ts, sacc, cs, preg, plo);
     pv_block<D, NT, PRECISE>(r.v, preg, plo, ts);
@@ -357,11 +382,11 @@ struct SplitPipe {
     }
     template <bool PRECISE>
     __device__ __forceinline__ void run(const ChunkCtx &ctx, int wave, int nblk, TileState<D> (&ts)[1], float cs,
-                                        float lazy) {
+                                        float inv_cs) {
         for (int blk = wave; blk < nblk; blk += 2 * kWaves) {
-            compute_block<D, 1, PRECISE>(b0, ctx, blk * 32, ts, cs, lazy);
+            compute_block<D, 1, PRECISE>(b0, ctx, blk * 32, ts, cs, inv_cs);
             load_block<D>(b0, ctx, (blk + 2 * kWaves) * 32, blk + 2 * kWaves < nblk);
-            if (blk + kWaves < nblk) compute_block<D, 1, PRECISE>(b1, ctx, (blk + kWaves) * 32, ts, cs, lazy);
+            if (blk + kWaves < nblk) compute_block<D, 1, PRECISE>(b1, ctx, (blk + kWaves) * 32, ts, cs, inv_cs);
             load_block<D>(b1, ctx, (blk + 3 * kWaves) * 32, blk + 3 * kWaves < nblk);
         }
     }
@@ -408,7 +433,7 @@ __device__ __forceinline__ void share_issue(Share<D, TR> &s, const ChunkCtx &c, 
 
 template <int D, int TR, int NT, bool PRECISE>
 __device__ __forceinline__ void share_step(Share<D, TR> &s, const ChunkCtx &c, u32x4 *xs, int t, int lane, int blk,
-                                           int next_blk, int nblk, TileState<D> (&ts)[NT], float cs, float lazy) {
+                                           int next_blk, int nblk, TileState<D> (&ts)[NT], float cs, float inv_cs) {
     constexpr int KK = D / 32;
     const bool live = blk < nblk;
     if (live) {
@@ -434,21 +459,17 @@ __device__ __forceinline__ void share_step(Share<D, TR> &s, const ChunkCtx &c, u
             for (int kk = 0; kk < KK; ++kk) r.k[aa][kk] = __builtin_bit_cast(bf16x8, xs[(aa * KK + kk) * 64 + lane]);
 #pragma unroll
         for (int j = 0; j < 8; ++j) r.v[j] = xs[(2 * KK + j) * 64 + lane];
-        compute_block<D, NT, PRECISE>(r, c, blk * 32, ts, cs, lazy);
+        compute_block<D, NT, PRECISE>(r, c, blk * 32, ts, cs, inv_cs);
     }
 }
 
-// NT = row tiles per wave.  A block read back from LDS serves all NT tiles of the wave: with one tile per
-// wave the four waves of a workgroup pull 4 x 16 KB through LDS per block, twice what the MFMAs of the block
-// take, so groups wider than four tiles run two tiles per wave (LDS and MFMA time then balance).
+// Used for tasks of two row tiles (TR = 2, NT = 1: two waves per tile, the two pairs take alternate blocks);
+// wider tasks go through WidePipe below.
 template <int D, int TR, int NT>
 struct SharedPipe {
     using S = Share<D, TR>;
     static constexpr int NP = kWaves / TR;  // token parts: part p takes blocks p, p+NP, ...
-    // blocks whose shares a wave keeps in flight.  A wave's share of a block is small (1/TR of it), and with a
-    // tile per wave of four, one block ahead measured fastest (a 64-row group over a 4000-token prefix: 20.0 us
-    // against 22.3 us with four ahead): what is queued deeper only waits behind the other workgroup's loads.
-    static constexpr int DEPTH = (NT == 1 && TR == 4) ? 1 : 2;
+    static constexpr int DEPTH = 2;  // blocks whose shares a wave keeps in flight
     Share<D, TR> st[DEPTH];
     __device__ __forceinline__ void prime(const ChunkCtx &ctx, int wave, int nblk) {
         const int t = wave % TR, part = wave / TR;
@@ -457,7 +478,7 @@ struct SharedPipe {
     }
     template <bool PRECISE>
     __device__ __forceinline__ void run(const ChunkCtx &ctx, u32x4 *xbuf, int wave, int lane, int nblk,
-                                        TileState<D> (&ts)[NT], float cs, float lazy) {
+                                        TileState<D> (&ts)[NT], float cs, float inv_cs) {
         const int t = wave % TR, part = wave / TR;
         const int iters = (nblk + NP - 1) / NP;  // the same for every wave: barriers stay aligned
         u32x4 *xb = xbuf + (size_t)part * 2 * S::NSLOT * 64;
@@ -470,7 +491,7 @@ struct SharedPipe {
                 // LDS exchange stages alternate; stage (it & 1) was last read two steps ago, before the
                 // barrier of the previous step
                 share_step<D, TR, NT, PRECISE>(st[u], ctx, xb + (it & 1) * S::NSLOT * 64, t, lane, blk, blk + DEPTH * NP, nblk,
-                                      ts, cs, lazy);
+                                      ts, cs, inv_cs);
             }
         }
     }
@@ -490,7 +511,10 @@ template <int D, int NT, bool UNIFORM>
 struct WidePipe {
     static constexpr int KK = D / 32;
     using S = Share<D, 4>;
-    static constexpr int DEPTH = NT == 1 ? 1 : 2;  // blocks whose shares a wave keeps in flight (see SharedPipe)
+    // blocks whose shares a wave keeps in flight: with a tile per wave one measured faster than two (a 64-row
+    // group over a 4000-token prefix: 19.5 us against 20.5 us); such a task is short and what is queued deeper
+    // only waits behind the other workgroup's loads
+    static constexpr int DEPTH = NT == 1 ? 1 : 2;
     S st[DEPTH];
     uint32_t lane_row, lane_col;  // UNIFORM: first row of this lane's loads inside a block, byte offset inside a row
 
@@ -532,8 +556,18 @@ struct WidePipe {
 #pragma unroll
             for (int q = 0; q < KK; ++q) xs[(t * KK + q) * 64 + lane] = sh.x[q];
         } else {
+            // V: this wave holds tokens 16(t-2) + 4g + {0..3}, i.e. the token pairs p = 2(t-2) and 2(t-2) + 1 of
+            // every lane's eight; it interleaves them once for all four waves (pv_block, READY) and writes its
+            // half (8 bytes) of each of the eight operand images
+            uint2 *xh = reinterpret_cast<uint2 *>(xs + 2 * KK * 64) + (t - 2);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) xs[(2 * KK + 4 * (t - 2) + q) * 64 + lane] = sh.x[q];
+            for (int c2 = 0; c2 < 4; ++c2) {
+                const uint32_t lo0 = sh.x[0][c2], hi0 = sh.x[1][c2], lo1 = sh.x[2][c2], hi1 = sh.x[3][c2];
+                xh[((2 * c2) * 64 + lane) * 2] = make_uint2(__builtin_amdgcn_perm(hi0, lo0, 0x05040100u),
+                                                            __builtin_amdgcn_perm(hi1, lo1, 0x05040100u));
+                xh[((2 * c2 + 1) * 64 + lane) * 2] = make_uint2(__builtin_amdgcn_perm(hi0, lo0, 0x07060302u),
+                                                                __builtin_amdgcn_perm(hi1, lo1, 0x07060302u));
+            }
         }
         __syncthreads();
         issue(sh, c, t, next_blk, nblk);
@@ -553,7 +587,7 @@ struct WidePipe {
     template <bool PRECISE>
     __device__ __forceinline__ void step(S &sh, const ChunkCtx &c, u32x4 *xs, int t, int lane, int blk, int nblk,
                                          TileState<D> (&ts)[NT], f32x4 (&sacc)[NT][2], u32x4 (&vreg)[8], float cs,
-                                         float lazy) {
+                                         float inv_cs) {
         exchange(sh, c, xs, t, lane, blk + DEPTH, nblk);
         bf16x8 k[2][KK];
         read_k(xs, lane, k);
@@ -561,10 +595,11 @@ struct WidePipe {
         f32x4 snew[NT][2];
         weights_block<D, NT, PRECISE>(ts, sacc, cs, preg, plo);
         qk_block<D, NT>(k, ts, snew);
-        pv_block<D, NT, PRECISE>(vreg, preg, plo, ts);
+        pv_block<D, NT, PRECISE, true>(vreg, preg, plo, ts);
         read_v(xs, lane, vreg);
         mask_block<D, NT>(c, blk * 32, ts, snew);
-        raise_block<D, NT>(ts, snew, cs, lazy);
+        shift_block<D, NT>(ts, snew, cs);
+        raise_block<D, NT>(ts, snew);
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) {
             sacc[tt][0] = snew[tt][0];
@@ -574,7 +609,7 @@ struct WidePipe {
 
     template <bool PRECISE>
     __device__ __forceinline__ void run(const ChunkCtx &ctx, u32x4 *xbuf, int wave, int lane, int nblk,
-                                        TileState<D> (&ts)[NT], float cs, float lazy) {
+                                        TileState<D> (&ts)[NT], float cs, float inv_cs) {
         const int t = wave;
         constexpr int STAGE = S::NSLOT * 64;  // u32x4 per LDS exchange stage; stage (blk & 1) holds block blk
         f32x4 sacc[NT][2];
@@ -586,7 +621,8 @@ struct WidePipe {
             qk_block<D, NT>(k, ts, sacc);
             read_v(xbuf, lane, vreg);
             mask_block<D, NT>(ctx, 0, ts, sacc);
-            raise_block<D, NT>(ts, sacc, cs, lazy);
+            shift_block<D, NT>(ts, sacc, cs);
+            raise_block<D, NT>(ts, sacc);
         }
         // steady state, DEPTH steps per round so that the shares in flight are addressed statically.  Whole
         // rounds only inside the loop (a round that could stop half way would make the compiler assume, for the
@@ -596,15 +632,15 @@ struct WidePipe {
 #pragma unroll
             for (int u = 0; u < DEPTH; ++u) {
                 const int blk = b0 + u;
-                step<PRECISE>(st[(1 + u) % DEPTH], ctx, xbuf + (blk & 1) * STAGE, t, lane, blk, nblk, ts, sacc, vreg, cs, lazy);
+                step<PRECISE>(st[(1 + u) % DEPTH], ctx, xbuf + (blk & 1) * STAGE, t, lane, blk, nblk, ts, sacc, vreg, cs, inv_cs);
             }
         }
         if (DEPTH == 2 && b0 < nblk)
-            step<PRECISE>(st[1], ctx, xbuf + (b0 & 1) * STAGE, t, lane, b0, nblk, ts, sacc, vreg, cs, lazy);
+            step<PRECISE>(st[1], ctx, xbuf + (b0 & 1) * STAGE, t, lane, b0, nblk, ts, sacc, vreg, cs, inv_cs);
         {   // last block: weights and products
             bf16x8 preg[NT], plo[NT];
             weights_block<D, NT, PRECISE>(ts, sacc, cs, preg, plo);
-            pv_block<D, NT, PRECISE>(vreg, preg, plo, ts);
+            pv_block<D, NT, PRECISE, true>(vreg, preg, plo, ts);
         }
     }
 };
@@ -731,7 +767,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
         ts[u].qpos = ok ? cqlo + pl : -1;
         q_user[u] = 0;
         if (ok) q_user[u] = a.q_order[cqlo + pl];
-        ts[u].rs = RowState{-INFINITY, 0.f, f32x4{0.f, 0.f, 0.f, 0.f}};
+        ts[u].rs = RowState{0.f, -INFINITY, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc) ts[u].o[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
@@ -747,34 +783,39 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
         }
         __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0)
     };
-    const float lazy = kLazyLog2 / a.c;
+    const float inv_cs = 1.0f / a.c;  // turns a reference in exponent units back into score units
     TileState<D>(&ts1)[1] = reinterpret_cast<TileState<D>(&)[1]>(ts);  // the one-tile paths use ts[0] only
 
     if (TR == 1) {
         SplitPipe<D> pipe;
         pipe.prime(ctx, wave, nblk);
         load_q(1);
-        pipe.template run<PRECISE>(ctx, wave, nblk, ts1, a.c, lazy);
+        pipe.template run<PRECISE>(ctx, wave, nblk, ts1, a.c, inv_cs);
     } else if (TR == 2) {
         SharedPipe<D, 2, 1> pipe;
         pipe.prime(ctx, wave, nblk);
         load_q(1);
-        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts1, a.c, lazy);
-    } else if (NTW == 1) {
-        SharedPipe<D, 4, 1> pipe;
+        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts1, a.c, inv_cs);
+    } else if (NTW == 1 && ctx.uniform) {
+        WidePipe<D, 1, D == 128> pipe;
         pipe.prime(ctx, wave, nblk);
         load_q(1);
-        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts1, a.c, lazy);
+        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts1, a.c, inv_cs);
+    } else if (NTW == 1) {
+        WidePipe<D, 1, false> pipe;
+        pipe.prime(ctx, wave, nblk);
+        load_q(1);
+        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts1, a.c, inv_cs);
     } else if (ctx.uniform) {
         WidePipe<D, 2, D == 128> pipe;  // the fast addressing is written for four loads per K loader
         pipe.prime(ctx, wave, nblk);
         load_q(2);
-        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts, a.c, lazy);
+        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts, a.c, inv_cs);
     } else {
         WidePipe<D, 2, false> pipe;
         pipe.prime(ctx, wave, nblk);
         load_q(2);
-        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts, a.c, lazy);
+        pipe.template run<PRECISE>(ctx, xbuf, wave, lane, nblk, ts, a.c, inv_cs);
     }
 
     // ---- merge the token parts in LDS and write one partial result per (chunk, row):
@@ -789,7 +830,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void deft_stage1(Stage1Args a) {
         const float l_tot = ts[u].rs.l[0];
         __syncthreads();
         if (g == 0) {
-            mM[wave * 16 + n16] = ts[u].rs.m;
+            mM[wave * 16 + n16] = ts[u].rs.m(inv_cs);
             mL[wave * 16 + n16] = l_tot;
         }
         if (D == 128 || g < 2) {
