@@ -626,11 +626,12 @@ extern "C" int32_t deft_suggest_chunk_size(const int32_t *node_tok_len, const in
         }
         if (mode == DEFT_SPLIT_BALANCED) {
             // The balanced split stretches the chunks of wide groups by itself, so the size asked for is that of
-            // a narrow chunk: one dispatch round of them if the tree is small, 768 tokens otherwise (measured on
-            // the reasoning and long-context trees: two rounds of 768-token tasks beat one round of longer ones,
-            // because the long tasks of the wide groups then share compute units with streaming narrow ones).
+            // a narrow chunk: one dispatch round of them if the tree is small, 1024 tokens otherwise (measured on
+            // the reasoning and long-context trees: 1024 and 1280 are level, 768 costs 2-3 %, 1536 and above 30 %:
+            // the chunks of the widest groups then reach the 4096-token limit and leave too few tasks to share
+            // compute units with the streaming narrow ones).
             int64_t chunk = ((int64_t)(reached_tokens * Hkv / 512.0L) + 127) / 128 * 128;
-            return (int32_t)std::max<int64_t>(128, std::min<int64_t>(768, chunk));
+            return (int32_t)std::max<int64_t>(128, std::min<int64_t>(1024, chunk));
         }
         const long double per_task = task_tokens * Hkv / 512.0L;
         // a multiple of 128 tokens = 4 waves x 32-token blocks, so a token-split task gives every wave the same work.
