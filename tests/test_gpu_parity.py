@@ -227,6 +227,27 @@ def test_wide_groups_and_many_row_tiles():
     check(got, reference(t, Q, K, V), strict=False, abs_v=reference_abs_v(t, Q, K, V), two_term=True)
 
 
+@pytest.mark.parametrize("root_len", [1, 2, 3, 31, 33, 34, 35, 63, 64, 65, 97, 161])
+@pytest.mark.parametrize("nq,G", [(12, 4), (20, 4), (30, 4)])  # 48, 80 and 120 rows: 3, 5 and 8 row tiles
+def test_wide_single_piece_chunks_with_ragged_last_blocks(root_len, nq, G):
+    """Wide groups over one node whose last 32-token block holds 1, 2, 3 ... rows, both paths of the pipelined
+    loop (a tile per wave, two tiles per wave), long paths (bf16 weights) and short ones, d = 128 (addressed
+    from a block pointer and a clamped row) and d = 64 (general addressing).  The clamp of the last block's
+    rows is what these shapes exercise: the loads of a wave that fetches V cover four consecutive rows."""
+    for d in (128, 64):
+        for pad in (0, 1100):  # pad: a second, long node above the shared one lifts every path over 1024 tokens
+            if pad:
+                lens, par, qn = [pad, root_len] + [1] * nq, [-1, 0] + [1] * nq, list(range(2, nq + 2))
+            else:
+                lens, par, qn = [root_len] + [1] * nq, [-1] + [0] * nq, list(range(1, nq + 1))
+            t = wl._finish("ragged", lens, par, qn, 2 * G, 2, d, 500 + root_len + nq)
+            Q, K, V = wl.make_qkv(t)
+            ref = reference(t, Q, K, V)
+            for mode in ("flatten", "node"):
+                got, _ = run_gpu(t, Q, K, V, chunk_size=4096, out_dtype=torch.float32, mode=mode)
+                check(got, ref, strict=False)
+
+
 def test_explicit_scale_and_empty_paths():
     t = wl.random_tree(3, n_nodes=6, max_len=50, nq=5, Hq=4, Hkv=2, d=128)
     Q, K, V = wl.make_qkv(t)
