@@ -204,7 +204,7 @@ int deft_plan_paged_update(const deft_plan_t *prev, const int32_t *node_page_ptr
  * A chunk size S_t suited to this tree on an MI355X (the paper leaves S_t as a tuning knob, Fig. 11).
  * flags names the split the size is for (a DEFT_SPLIT_* / DEFT_GROUP_QUERY value; other bits are ignored).
  * For DEFT_SPLIT_BALANCED: the multiple of 128 that gives about one stage-1 task per resident workgroup slot
- * (two per compute unit) if all chunks were narrow, at least 128 and at most 768 (the split itself makes the
+ * (two per compute unit) if all chunks were narrow, at least 128 and at most 1024 (the split itself makes the
  * chunks of widely shared nodes up to four times longer).  For the other splits: the multiple of 128 that
  * makes the number of stage-1 tasks, (chunk, KV head, 128 rows of the chunk's query group), about twice the
  * number of compute units, so that every unit streams the same number of KV bytes; at least 128 and at most
