@@ -897,7 +897,7 @@ __global__ __launch_bounds__(64) void deft_stage2(Stage2Args a) {
     const int lane = threadIdx.x;
     const int p = blockIdx.x / a.Hq;
     const int qh = blockIdx.x - p * a.Hq;
-    // one 64-byte record per query: how many partials, where the result goes, the first slot ids
+    // one 128-byte record per query: how many partials, where the result goes, the first slot ids
     const int hd = a.q_head[(size_t)p * deft::kQueryHeadInts + (lane & (deft::kQueryHeadInts - 1))];
     const int n = __shfl(hd, 0);
     const int q_user = __shfl(hd, 1);

@@ -18,7 +18,7 @@ constexpr int kItemInts = 16;
 constexpr int kMaxTilesPerTask = 8;
 // Stage 2 reads one kQueryHeadInts-int32 record per plan query: {number of partials n, caller's query index,
 // the first kQueryInlineSlots slot ids}; queries with more partials go on to the CSR lists.
-constexpr int kQueryHeadInts = 16;
+constexpr int kQueryHeadInts = 32;
 constexpr int kQueryInlineSlots = kQueryHeadInts - 2;
 enum ItemField {
     kItChunk = 0,     // chunk id
